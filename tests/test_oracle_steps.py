@@ -1,0 +1,280 @@
+"""Pins of the oracle's optimizer steps (moments, error feedback across steps, the
+two placements of the moments) against closed forms, identities of the paper's
+analysis, a library Adam and fp64 re-derivations that do not share its code."""
+import numpy as np
+import pytest
+
+from oracle.qadam_oracle import OracleConfig
+
+
+def _zeros(n, k=1):
+    return [np.zeros(n, np.float32) for _ in range(k)]
+
+
+# ------------------------------------------------------------------ closed form
+def test_constant_gradient_closed_form(oracle):
+    """Algorithm 1 lines 3-5 with Q_g = Q_x = id and a constant gradient g:
+    m_t = (1 - beta^t) g, v_t = (1 - theta^t) g^2 (unrolling the recursions from m_0 = v_0 = 0),
+    x_{t+1} = x_t - alpha (1-beta^t) g / sqrt((1-theta^t) g^2 + eps): eps inside the root, no bias
+    correction.  beta != theta and a large eps make swapped or misplaced constants visible."""
+    n, T = 257, 25
+    beta, theta, eps, lr = 0.8, 0.95, 1e-4, 3e-3
+    rng = np.random.default_rng(0)
+    g = (rng.standard_normal(n) * 1e-2).astype(np.float32)
+    x0 = rng.standard_normal(n).astype(np.float32)
+    cfg = OracleConfig(identity_g=1, identity_x=1, beta1=beta, eps=eps, weight_ef=0)
+    x = x0.copy()
+    m, v, e, w = _zeros(n, 4)
+    b32, t32, e32, l32 = (np.float64(np.float32(c)) for c in (beta, theta, eps, lr))
+    g64 = g.astype(np.float64)
+    x_ref = x0.astype(np.float64)
+    for t in range(1, T + 1):
+        oracle.step_s(cfg, [0, n], t, lr, theta, [g], [e], x, m, v, w)
+        m_ref = (1 - b32 ** t) * g64
+        v_ref = (1 - t32 ** t) * g64 ** 2
+        x_ref = x_ref - l32 * m_ref / np.sqrt(v_ref + e32)
+        assert np.allclose(m, m_ref, rtol=2e-6, atol=1e-12)
+        assert np.allclose(v, v_ref, rtol=2e-6, atol=1e-14)
+        assert np.allclose(x, x_ref, rtol=2e-6, atol=1e-7)
+    assert not e.any()
+
+
+def test_identity_quantizers_reduce_to_generic_adam(oracle):
+    """Sec. 3.1.1 / 3.1.2 / after Theorem 3: with Q_g and Q_x the identity the method is
+    (distributed) generic Adam.  Variant S must equal an fp64 generic Adam on the mean gradient;
+    with one worker variants S and W and Algorithm 1 coincide bit for bit."""
+    n, T, N = 1000, 30, 4
+    beta, theta, eps, lr = 0.9, 0.999, 1e-5, 1e-3
+    rng = np.random.default_rng(1)
+    segs = [0, 100, 100, 613, n]
+    cfg = OracleConfig(identity_g=1, identity_x=1, beta1=beta, eps=eps)
+    x0 = (rng.standard_normal(n) * 0.02).astype(np.float32)
+    x = x0.copy()
+    m, v, w = _zeros(n, 3)
+    errs = _zeros(n, N)
+    xr = x0.astype(np.float64)
+    mr = np.zeros(n)
+    vr = np.zeros(n)
+    b, th, ep, l = (np.float64(np.float32(c)) for c in (beta, theta, eps, lr))
+    x1 = x0.copy(); m1, v1, w1 = _zeros(n, 3); e1 = _zeros(n, 1)
+    x2 = x0.copy(); w2 = _zeros(n, 1)[0]; e2 = _zeros(n, 1); mw = _zeros(n, 1); vw = _zeros(n, 1)
+    for t in range(1, T + 1):
+        grads = [(rng.standard_normal(n) * 1e-2).astype(np.float32) for _ in range(N)]
+        oracle.step_s(cfg, segs, t, lr, theta, grads, errs, x, m, v, w)
+        gbar = np.mean(np.stack(grads).astype(np.float64), axis=0)
+        vr = th * vr + (1 - th) * gbar ** 2
+        mr = b * mr + (1 - b) * gbar
+        xr = xr - l * mr / np.sqrt(vr + ep)
+        assert np.allclose(x, xr, rtol=1e-6, atol=1e-7)
+        assert np.allclose(m, mr, rtol=1e-5, atol=1e-9)
+        assert np.allclose(v, vr, rtol=1e-5, atol=1e-12)
+        # N = 1: S == W == Algorithm 1
+        oracle.step_s(cfg, segs, t, lr, theta, grads[:1], e1, x1, m1, v1, w1)
+        oracle.step_w(cfg, segs, t, lr, theta, grads[:1], e2, mw, vw, x2, w2)
+        assert np.array_equal(x1, x2) and np.array_equal(m1, mw[0]) and np.array_equal(v1, vw[0])
+
+
+def test_bias_corrected_flavour_matches_library_adam(oracle):
+    """The textbook special case (bias correction, eps outside the root) against torch.optim.Adam
+    on CPU in fp32; independent of the paper's flavour, it pins the moment recursions and the
+    worker averaging."""
+    torch = pytest.importorskip("torch")
+    n, T, N = 512, 20, 2
+    beta, theta, eps, lr = 0.9, 0.99, 1e-3, 1e-2
+    rng = np.random.default_rng(2)
+    x0 = rng.standard_normal(n).astype(np.float32)
+    cfg = OracleConfig(identity_g=1, identity_x=1, beta1=beta, eps=eps, adam_flavor=1)
+    x = x0.copy()
+    m, v, w = _zeros(n, 3)
+    errs = _zeros(n, N)
+    xt = torch.tensor(x0.copy(), requires_grad=True)
+    opt = torch.optim.Adam([xt], lr=lr, betas=(beta, theta), eps=eps)
+    for t in range(1, T + 1):
+        grads = [(rng.standard_normal(n) * 1e-2).astype(np.float32) for _ in range(N)]
+        oracle.step_s(cfg, [0, n], t, lr, theta, grads, errs, x, m, v, w)
+        xt.grad = torch.tensor((grads[0] + grads[1]) / np.float32(2))
+        opt.step()
+        assert np.allclose(x, xt.detach().numpy(), rtol=1e-5, atol=1e-6)
+
+
+def test_theta_schedule_argument(oracle):
+    """Assumption 4: theta_t = 1 - theta/t and alpha_t = alpha/sqrt(t) are per-step arguments."""
+    n, T = 64, 12
+    rng = np.random.default_rng(3)
+    cfg = OracleConfig(identity_g=1, identity_x=1, beta1=0.9, eps=1e-6)
+    x = np.zeros(n, np.float32)
+    m, v, w = _zeros(n, 3)
+    e = _zeros(n, 1)
+    xr = np.zeros(n); mr = np.zeros(n); vr = np.zeros(n)
+    for t in range(1, T + 1):
+        g = rng.standard_normal(n).astype(np.float32)
+        th = np.float32(1 - 0.5 / t)
+        lr = np.float32(1e-2 / np.sqrt(t))
+        oracle.step_s(cfg, [0, n], t, float(lr), float(th), [g], e, x, m, v, w)
+        vr = np.float64(th) * vr + (1 - np.float64(th)) * g.astype(np.float64) ** 2
+        mr = np.float64(np.float32(0.9)) * mr + (1 - np.float64(np.float32(0.9))) * g
+        xr = xr - np.float64(lr) * mr / np.sqrt(vr + np.float64(np.float32(1e-6)))
+        assert np.allclose(x, xr, rtol=2e-6, atol=1e-7)
+
+
+# ------------------------------------------------------------ error feedback
+@pytest.mark.parametrize("k_g", [0, 2])
+def test_error_feedback_telescoping_variant_s(oracle, k_g):
+    """Notation 1 (x~_t = x_t - e_t telescopes): what a worker has sent plus what it still holds
+    equals what it was given, sum_t q_t = sum_t g_t - e_{T+1}; and the residual stays bounded
+    (lemma on ||e_t||)."""
+    n, T, N = 3000, 40, 3
+    rng = np.random.default_rng(10 + k_g)
+    segs = [0, 1000, 1024, n]
+    cfg = OracleConfig(k_g=k_g, k_x=6)
+    errs = _zeros(n, N)
+    sum_q = [np.zeros(n) for _ in range(N)]
+    sum_g = [np.zeros(n) for _ in range(N)]
+    for t in range(1, T + 1):
+        for i in range(N):
+            g = (rng.standard_normal(n) * 1e-2).astype(np.float32)
+            out = oracle.worker_quantize(cfg, segs, i, t, g, errs[i], want_q=True)
+            sum_q[i] += out["q"]
+            sum_g[i] += g
+            # decoded packed codes are the same numbers
+            codes = oracle.unpack_all(k_g, segs, out["words"])
+            assert np.array_equal(codes, out["codes"])
+    for i in range(N):
+        assert np.allclose(sum_q[i], sum_g[i] - errs[i], rtol=0, atol=1e-6)
+        assert np.max(np.abs(errs[i])) < 0.2      # a few gradient magnitudes, not growing with T
+
+
+def test_variant_w_telescoping(oracle):
+    """Notation 3: x~_t = x_t - mean_i e_t^(i) follows the un-quantized recursion
+    x~_{t+1} = x~_t + mean_i Delta_t^(i), Delta = -alpha m / sqrt(v + eps) with the workers' own
+    moments (Algorithm 3 lines 4-5).  The gradients are given, so the right-hand side is an fp64
+    per-worker generic Adam that never sees a quantizer."""
+    n, T, N = 2048, 30, 4
+    beta, theta, eps, lr = 0.9, 0.999, 1e-5, 1e-3
+    rng = np.random.default_rng(20)
+    cfg = OracleConfig(k_g=2, k_x=6, beta1=beta, eps=eps, weight_ef=1)
+    x0 = (rng.standard_normal(n) * 0.02).astype(np.float32)
+    x = x0.copy()
+    errs, mw, vw = _zeros(n, N), _zeros(n, N), _zeros(n, N)
+    werr = np.zeros(n, np.float32)
+    b, th, ep, l = (np.float64(np.float32(c)) for c in (beta, theta, eps, lr))
+    mr = [np.zeros(n) for _ in range(N)]
+    vr = [np.zeros(n) for _ in range(N)]
+    xt = x0.astype(np.float64)
+    for t in range(1, T + 1):
+        grads = [(rng.standard_normal(n) * 1e-2).astype(np.float32) for _ in range(N)]
+        out = oracle.step_w(cfg, [0, 2000, n], t, lr, theta, grads, errs, mw, vw, x, werr)
+        assert out["status"] == 0
+        upd = np.zeros(n)
+        for i in range(N):
+            g = grads[i].astype(np.float64)
+            vr[i] = th * vr[i] + (1 - th) * g * g
+            mr[i] = b * mr[i] + (1 - b) * g
+            upd += l * mr[i] / np.sqrt(vr[i] + ep)
+            assert np.allclose(mw[i], mr[i], rtol=1e-5, atol=1e-9)
+        xt = xt - upd / N
+        x_tilde = x.astype(np.float64) - np.mean(np.stack(errs).astype(np.float64), axis=0)
+        assert np.allclose(x_tilde, xt, rtol=0, atol=2e-6)
+    # the quantizer really was active: iterate differs from the un-quantized one
+    assert np.max(np.abs(x.astype(np.float64) - xt)) > 1e-5
+
+
+def test_variant_s_server_mean_and_order(oracle):
+    """Algorithm 2 line 3 (mean of the N worker messages) applied to dequantized gradients: the
+    server's m after one step from zero is (1-beta) * mean_i q_i, with the q_i decoded
+    independently here from the packed words and scales."""
+    n, N = 1500, 8
+    rng = np.random.default_rng(30)
+    segs = [0, 700, n]
+    cfg = OracleConfig(k_g=2, k_x=6, beta1=0.75, eps=1e-8)
+    grads = [(rng.standard_normal(n) * 10.0 ** rng.uniform(-3, 0)).astype(np.float32) for _ in range(N)]
+    errs = _zeros(n, N)
+    x = np.zeros(n, np.float32)
+    m, v, w = _zeros(n, 3)
+    out = oracle.step_s(cfg, segs, 1, 1e-3, 0.5, grads, errs, x, m, v, w)
+    w_mu = oracle.grad_code_bits(2) - 1
+    tot = np.zeros(n)
+    for i in range(N):
+        codes = oracle.unpack_all(2, segs, out["words"][i]).astype(np.int64)
+        mu = codes & ((1 << w_mu) - 1)
+        sign = np.where(codes >> w_mu == 1, -1.0, 1.0)
+        scale = np.concatenate([np.full(700, out["scales"][i][0], np.float64),
+                                np.full(n - 700, out["scales"][i][1], np.float64)])
+        q = np.where(mu == 0, 0.0, sign * scale * 2.0 ** (mu - 1.0 - 2))
+        assert np.array_equal((grads[i].astype(np.float64) - q).astype(np.float32), errs[i])
+        tot += q
+    gbar = tot / N
+    # fp32 accumulation over 8 terms of mixed magnitude: absolute slack tied to the largest term
+    big = max(float(np.max(sc)) for sc in out["scales"])
+    assert np.allclose(m, 0.25 * gbar, rtol=1e-6, atol=1e-7 * big)
+    assert np.allclose(v, 0.5 * gbar ** 2, rtol=1e-5, atol=1e-7 * big ** 2)
+    assert np.allclose(x, -1e-3 * 0.25 * gbar / np.sqrt(0.5 * gbar ** 2 + 1e-8), rtol=1e-4, atol=1e-8)
+
+
+def test_fused_step_equals_three_calls(oracle):
+    """The whole step is exactly worker_quantize (per worker) + server_step + weight_quantize."""
+    n, N, T = 5000, 4, 6
+    rng = np.random.default_rng(40)
+    segs = [0, 64, 3000, 3001, n]
+    for k_g, k_x, wef, rnd in [(2, 6, 1, 0), (0, 14, 0, 0), (2, 6, 1, 1)]:
+        cfg = OracleConfig(k_g=k_g, k_x=k_x, weight_ef=wef, rounding=rnd, seed=99)
+        x0 = (rng.standard_normal(n) * 0.02).astype(np.float32)
+        xa, xb = x0.copy(), x0.copy()
+        ma, va, wa = _zeros(n, 3)
+        mb, vb, wb = _zeros(n, 3)
+        ea, eb = _zeros(n, N), _zeros(n, N)
+        for t in range(1, T + 1):
+            grads = [(rng.standard_normal(n) * 1e-2).astype(np.float32) for _ in range(N)]
+            oa = oracle.step_s(cfg, segs, t, 1e-3, 0.999, grads, ea, xa, ma, va, wa)
+            outs = [oracle.worker_quantize(cfg, segs, i, t, grads[i], eb[i]) for i in range(N)]
+            oracle.server_step(cfg, segs, t, 1e-3, 0.999, [o["words"] for o in outs],
+                               [o["scales"] for o in outs], xb, mb, vb)
+            ob = oracle.weight_quantize(cfg, t, xb, wb)
+            for i in range(N):
+                assert np.array_equal(oa["words"][i], outs[i]["words"])
+                assert np.array_equal(oa["scales"][i], outs[i]["scales"])
+                assert np.array_equal(ea[i], eb[i])
+            for a, b in [(xa, xb), (ma, mb), (va, vb), (wa, wb), (oa["wcodes"], ob["wcodes"])]:
+                assert np.array_equal(a, b)
+
+
+def test_layers_are_independent(oracle):
+    """The scale is per layer segment and everything else is element-wise, so running a layer
+    alone (with its global index base) gives the same bits as running it inside the vector --
+    the property that lets large configurations be checked layer by layer."""
+    n, N = 4000, 2
+    rng = np.random.default_rng(50)
+    segs = [0, 1000, 2500, n]
+    for rnd in (0, 1):
+        cfg = OracleConfig(k_g=2, k_x=6, rounding=rnd, seed=5)
+        grads = [(rng.standard_normal(n) * 1e-2).astype(np.float32) for _ in range(N)]
+        x0 = (rng.standard_normal(n) * 0.02).astype(np.float32)
+        x = x0.copy(); m, v, w = _zeros(n, 3); errs = _zeros(n, N)
+        full = oracle.step_s(cfg, segs, 3, 1e-3, 0.999, grads, errs, x, m, v, w)
+        a, b = segs[1], segs[2]
+        xs = x0[a:b].copy(); ms, vs, ws = _zeros(b - a, 3); es = _zeros(b - a, N)
+        part = oracle.step_s(cfg, [0, b - a], 3, 1e-3, 0.999, [g[a:b].copy() for g in grads], es,
+                             xs, ms, vs, ws, index_base=a)
+        assert np.array_equal(xs, x[a:b]) and np.array_equal(ws, w[a:b])
+        assert np.array_equal(part["wcodes"], full["wcodes"][a:b])
+        for i in range(N):
+            assert np.array_equal(es[i], errs[i][a:b])
+            assert part["scales"][i][0] == full["scales"][i][1]
+
+
+def test_window_equals_layer(oracle):
+    """Given the layer's scale, a window of the layer quantizes to the same codes."""
+    n = 10000
+    rng = np.random.default_rng(60)
+    g = (rng.standard_normal(n) * 1e-2).astype(np.float32)
+    e = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+    for rnd in (0, 1):
+        cfg = OracleConfig(k_g=2, rounding=rnd, seed=11)
+        err = e.copy()
+        full = oracle.worker_quantize(cfg, [0, n], 1, 4, g, err, index_base=128)
+        s = full["scales"][0]
+        assert s == np.max(np.abs(g + e))
+        a, b = 3000, 4111
+        ew = e[a:b].copy()
+        code, tie, q = oracle.worker_quantize_window(cfg, g[a:b].copy(), ew, s, j0=128 + a, step=4, worker=1)
+        assert np.array_equal(code, full["codes"][a:b]) and np.array_equal(ew, err[a:b])

@@ -1,0 +1,166 @@
+/*
+ * qadam.h -- C boundary of the MI355X (gfx950) library for the optimizer step of
+ * Quantized Adam with error feedback (arXiv 2004.14180).
+ *
+ * The step, per parameter (notation of the paper: x iterate, m and v moments, e error-feedback
+ * term, alpha_t step size, beta momentum, theta_t averaging parameter, N workers):
+ *
+ *   worker i :  p = g_i + e_i                         error-feedback add   (Alg. 1 line 5, Alg. 3 line 6)
+ *               s_il = ||p||_inf over layer l        scale of Q_g         (Sec. 5.1)
+ *               q = Q_g(p) = s * nearest point of G  G = {0, +-2^-k_g, ..., +-1/2, +-1}   (Sec. 5.1)
+ *               e_i <- p - q                          residual             (Alg. 1 line 6, Alg. 3 line 7)
+ *   server   :  gbar = (1/N) sum_i q_i               mean of the messages (Alg. 2 line 3)
+ *               v <- theta_t v + (1-theta_t) gbar^2   (Alg. 1 line 3)
+ *               m <- beta m + (1-beta) gbar           (Alg. 1 line 4)
+ *               x <- x - alpha_t m / sqrt(v + eps)    (Alg. 1 line 5 without the quantizer)
+ *               x^ = Q_x(x [+ e^x]),  e^x <- (x [+ e^x]) - x^      (Sec. 5.1; Alg. 2 lines 2 and 6)
+ *
+ * This is "variant S": the workers quantize gradients and the server owns the moments.  The
+ * paper's Algorithms 2-3 keep the moments on the workers and quantize the Adam update instead
+ * ("variant W"); the entry points ending in _w implement that placement with the same kernels.
+ *
+ * All arithmetic is IEEE binary32, one rounding per operation (no fused multiply-add), subnormals
+ * kept, division and square root correctly rounded; integer codes are therefore reproducible bit
+ * for bit by a plain CPU implementation of the same formulas.
+ *
+ * Conventions
+ *   - Every pointer named *_dev (and every element of the pointer arrays) is DEVICE memory on the
+ *     current HIP device, 16-byte aligned, owned by the caller and alive until the stream has
+ *     passed the call.  Pointer arrays themselves and seg_offsets are HOST memory, read during
+ *     the call only.
+ *   - `stream` is a hipStream_t passed as void*.  Compute calls only enqueue work on it; they do
+ *     not synchronise.  Calls on one handle must be issued in stream order (they share the
+ *     handle's status word).
+ *   - The parameter vector is flat, P = seg_offsets[L] elements, split into L layer segments
+ *     [seg_offsets[l], seg_offsets[l+1]); empty segments are allowed.
+ *   - `step` is the 1-based iteration t.
+ *   - Return value: QADAM_OK or a negative error code; on error nothing was enqueued.
+ *     Non-finite scales (NaN/Inf in g + e) are data errors: they set a bit in the status word that
+ *     qadam_get_status reads; the outputs of that layer are then unspecified (codes stay in range).
+ *   - The library allocates only in qadam_init (tables proportional to P/4096 plus the segment
+ *     table) and frees in qadam_destroy.
+ *
+ * Packed gradient codes (one buffer per worker, qadam_grad_code_bytes bytes): a code is
+ * (sign << w) | mu with mu in 0..k_g+1 the grid level (0 = zero, mu >= 1 = 2^(mu-1-k_g)),
+ * w = ceil(log2(k_g+2)), b = 1 + w bits (k_g=0: 2 bits; k_g=1,2: 3 bits; k_g=3..6: 4 bits).
+ * Per segment, in segment order: groups of 32 consecutive elements, each group stored as b
+ * consecutive uint32 words where word k holds bit k of the 32 codes and bit n of a word belongs to
+ * element 32*group + n; a ragged last group is zero padded, and each segment is padded with zero
+ * words to a multiple of 16 bytes.  Exactly b bits per element (Tables 1-2: 3/32 and 2/32 of fp32).
+ * Weight codes: one signed integer j per element, x^ = j * 2^-(k_x+1), |j| <= 2^k_x, stored as int8
+ * when k_x <= 6 and int16 otherwise (Tables 1-2: 1/4 and 1/2 of fp32).
+ */
+#ifndef QADAM_H
+#define QADAM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define QADAM_OK        0
+#define QADAM_EINVAL   -1   /* bad argument (null pointer, worker out of range, bad config, bad segments) */
+#define QADAM_EALIGN   -2   /* a device pointer is not 16-byte aligned */
+#define QADAM_ERANGE   -3   /* size beyond what the library supports */
+#define QADAM_EHIP     -4   /* a HIP runtime call failed (see qadam_last_error) */
+
+#define QADAM_MAX_WORKERS 32
+
+/* status word bits */
+#define QADAM_STATUS_NONFINITE_SCALE 1u   /* some ||g+e||_inf was NaN or Inf */
+
+typedef struct qadam_ctx* qadam_handle_t;
+
+typedef struct {
+    uint32_t struct_size;   /* = sizeof(qadam_config_t) */
+    int32_t  k_g;           /* Q_g grid exponent count, 0..6 (0 = ternary)                     Sec. 5.1 */
+    int32_t  k_x;           /* Q_x grid: multiples of 2^-(k_x+1) on [-1/2, 1/2], 0..14          Sec. 5.1 */
+    int32_t  rounding;      /* 0 = nearest, a midpoint goes to the larger magnitude (the paper's arg-min);
+                               1 = unbiased stochastic rounding driven by Philox4x32-10 keyed on
+                               (seed; element index, step, worker, stream) */
+    int32_t  weight_ef;     /* 0 = e^x written (x - x^) but not fed back (the server keeps full-precision x,
+                               Alg. 2); 1 = Q_x sees x + e^x and e^x accumulates */
+    int32_t  adam_flavor;   /* 0 = the paper's generic Adam (eps inside the root, no bias correction);
+                               1 = bias-corrected moments and eps outside the root */
+    float    beta1;         /* beta */
+    float    eps;           /* epsilon */
+    uint64_t seed;          /* key of the random stream (rounding = 1) */
+} qadam_config_t;
+
+typedef struct {
+    uint32_t flags;         /* OR of QADAM_STATUS_* since init or the last reset */
+    uint32_t reserved;
+} qadam_status_t;
+
+/* Create a handle for one flat parameter vector.  seg_offsets: L+1 non-decreasing HOST values with
+ * seg_offsets[0] = 0; num_workers in 1..QADAM_MAX_WORKERS.  Allocates the handle's device tables on
+ * the current device. */
+int qadam_init(qadam_handle_t* out, const qadam_config_t* cfg,
+               const int64_t* seg_offsets, int32_t num_segments, int32_t num_workers);
+int qadam_destroy(qadam_handle_t h);
+
+/* Bytes of one worker's packed gradient codes for the whole vector (including segment padding),
+ * and of the weight codes. */
+size_t qadam_grad_code_bytes(qadam_handle_t h);
+size_t qadam_weight_code_bytes(qadam_handle_t h);
+int64_t qadam_num_params(qadam_handle_t h);
+
+/* Worker side (steps p = g+e, s = ||p||_inf per layer, Q_g, residual):
+ *   grad_dev   [P] in        stochastic gradient g_i
+ *   err_dev    [P] in/out    e_i -> p - Q_g(p)
+ *   codes_dev  out           packed codes, qadam_grad_code_bytes bytes
+ *   scales_dev [L] out       per-layer scales s_il (fp32)
+ * worker in [0, num_workers). */
+int qadam_worker_quantize(qadam_handle_t h, int32_t worker, int64_t step,
+                          const float* grad_dev, float* err_dev,
+                          void* codes_dev, float* scales_dev, void* stream);
+
+/* Server side (mean of the dequantized messages in worker order, moments, parameter step):
+ *   codes[i], scales[i]: worker i's outputs of qadam_worker_quantize, i = 0..N-1 (HOST arrays of
+ *   device pointers);  x, m, v [P] in/out.  lr = alpha_t, beta2 = theta_t. */
+int qadam_server_step(qadam_handle_t h, int64_t step, float lr, float beta2,
+                      const void* const* codes, const float* const* scales,
+                      float* x_dev, float* m_dev, float* v_dev, void* stream);
+
+/* Weight quantizer Q_x with its residual:
+ *   x_dev [P] in;  werr_dev [P]: in/out when weight_ef = 1, out only when 0 (may then be NULL);
+ *   wcodes_dev out, qadam_weight_code_bytes bytes. */
+int qadam_weight_quantize(qadam_handle_t h, int64_t step, const float* x_dev,
+                          float* werr_dev, void* wcodes_dev, void* stream);
+
+/* The whole step in one call: identical results, bit for bit, to qadam_worker_quantize for
+ * i = 0..N-1, then qadam_server_step, then qadam_weight_quantize, but each buffer makes one trip
+ * through memory in the main kernel (the scales need one earlier read of g and e).
+ * grads, errs, codes, scales: HOST arrays of N device pointers. */
+int qadam_step_fused(qadam_handle_t h, int64_t step, float lr, float beta2,
+                     const float* const* grads, float* const* errs,
+                     void* const* codes, float* const* scales,
+                     float* x_dev, float* m_dev, float* v_dev,
+                     float* werr_dev, void* wcodes_dev, void* stream);
+
+/* Variant W (Algorithms 2-3 as printed): the worker owns m_i, v_i and quantizes
+ * alpha_t m_i / sqrt(v_i + eps) + e_i; the server subtracts the mean of the messages.
+ *   qadam_worker_step_w: grad [P] in; mw, vw [P] in/out; err [P] in/out; codes, scales out.
+ *   qadam_server_apply_w: x [P] in/out from the N messages. */
+int qadam_worker_step_w(qadam_handle_t h, int32_t worker, int64_t step, float lr, float beta2,
+                        const float* grad_dev, float* mw_dev, float* vw_dev, float* err_dev,
+                        void* codes_dev, float* scales_dev, void* stream);
+int qadam_server_apply_w(qadam_handle_t h, int64_t step,
+                         const void* const* codes, const float* const* scales,
+                         float* x_dev, void* stream);
+
+/* Dequantize weight codes to fp32 (what a worker does with the broadcast of Alg. 2 line 2). */
+int qadam_weight_dequantize(qadam_handle_t h, const void* wcodes_dev, float* xhat_dev, void* stream);
+
+/* Read (and optionally clear) the status word.  Synchronises the given stream. */
+int qadam_get_status(qadam_handle_t h, qadam_status_t* out, int32_t clear, void* stream);
+
+/* Text of the last HIP error seen by this thread's calls (static storage). */
+const char* qadam_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

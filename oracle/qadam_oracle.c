@@ -99,7 +99,7 @@ float oq_qg_decode(int32_t k_g, float s, uint8_t code)
     int32_t mu = code & ((1 << w) - 1);
     int32_t neg = (code >> w) & 1;
     if (mu == 0) return 0.0f;
-    float q = ldexpf(s, mu - 1 - k_g);     /* s * 2^(mu-1-k_g), exact unless it underflows */
+    float q = s * level(k_g, mu);          /* ||p||_inf times the grid point; exact unless it underflows */
     return neg ? -q : q;
 }
 
@@ -111,6 +111,9 @@ static void qg_elements(const oq_config* cfg, const float* p, int64_t n, int64_t
     const int32_t k_g = cfg->k_g;
     const int32_t top = k_g + 1;
     const int32_t w = mu_bits(k_g);
+    float lv[16], mid[16];                 /* lv[c] = level c; mid[c] = midpoint of levels c-1 and c (exact) */
+    for (int32_t c = 0; c <= top + 1; ++c) lv[c] = level(k_g, c <= top ? c : top);
+    for (int32_t c = 1; c <= top; ++c) mid[c] = 0.5f * (lv[c - 1] + lv[c]);
     for (int64_t j = 0; j < n; ++j) {
         float r = p[j] / s;                /* g / ||g||_inf */
         float a = fabsf(r);                /* in [0, 1] */
@@ -119,14 +122,12 @@ static void qg_elements(const oq_config* cfg, const float* p, int64_t n, int64_t
         if (cfg->rounding == 0) {
             /* nearest point of G: the largest level whose lower midpoint is <= a
              * (a value on a midpoint goes to the level of larger magnitude) */
-            for (int32_t c = top; c >= 1; --c) {
-                float lo = level(k_g, c - 1), hi = level(k_g, c);
-                float mid = 0.5f * (lo + hi);          /* exact */
-                if (a >= mid) { mu = c; break; }
-            }
-            for (int32_t c = 1; c <= top; ++c) {
-                float mid = 0.5f * (level(k_g, c - 1) + level(k_g, c));
-                if (fabs((double)a - (double)mid) <= (double)ulp_above(a)) flagged = 1;
+            for (int32_t c = top; c >= 1; --c)
+                if (a >= mid[c]) { mu = c; break; }
+            if (tie) {
+                double ulp = (double)ulp_above(a);
+                for (int32_t c = 1; c <= top; ++c)
+                    if (fabs((double)a - (double)mid[c]) <= ulp) flagged = 1;
             }
         } else {
             /* unbiased rounding between the two neighbours lo <= a < hi */
@@ -135,8 +136,8 @@ static void qg_elements(const oq_config* cfg, const float* p, int64_t n, int64_t
             } else {
                 int32_t below = 0;
                 for (int32_t c = top; c >= 1; --c)
-                    if (a >= level(k_g, c)) { below = c; break; }
-                float lo = level(k_g, below), hi = level(k_g, below + 1);
+                    if (a >= lv[c]) { below = c; break; }
+                float lo = lv[below], hi = lv[below + 1];
                 float frac = (a - lo) / (hi - lo);
                 float U = oq_uniform24(cfg->seed, j0 + j, step, worker, 0);
                 mu = below + (U < frac ? 1 : 0);
@@ -145,7 +146,10 @@ static void qg_elements(const oq_config* cfg, const float* p, int64_t n, int64_t
         int32_t neg = (p[j] < 0.0f) && (mu > 0);
         uint8_t c8 = (uint8_t)((neg << w) | mu);
         if (code) code[j] = c8;
-        if (q) q[j] = oq_qg_decode(k_g, s, c8);
+        if (q) {
+            float qa = (mu == 0) ? 0.0f : s * lv[mu];
+            q[j] = neg ? -qa : qa;
+        }
         if (tie) tie[j] = flagged;
     }
 }
@@ -219,8 +223,10 @@ void oq_qx(const oq_config* cfg, const float* y, int64_t n, int64_t j0, int64_t 
 {
     const int32_t k_x = cfg->k_x;
     const float jmax = ldexpf(1.0f, k_x);
+    const float per_unit = ldexpf(1.0f, k_x + 1);     /* 1 / grid spacing of Q_x, a power of two */
+    const float spacing = ldexpf(1.0f, -(k_x + 1));
     for (int64_t i = 0; i < n; ++i) {
-        float u = ldexpf(y[i], k_x + 1);   /* 2x in units of the grid spacing; exact */
+        float u = y[i] * per_unit;         /* 2x in units of the spacing of X; exact scaling */
         float jf;
         uint8_t flagged = 0;
         if (isnan(u)) {
@@ -228,7 +234,7 @@ void oq_qx(const oq_config* cfg, const float* y, int64_t n, int64_t j0, int64_t 
         } else {
             if (cfg->rounding == 0) {
                 jf = roundf(u);            /* nearest, halves away from zero */
-                if (fabsf(u) < 0x1p23f) {
+                if (tie && fabsf(u) < 0x1p23f) {
                     double h = floor((double)u) + 0.5;
                     if (fabs((double)u - h) <= (double)ulp_above(fabsf(u))) flagged = 1;
                 }
@@ -240,7 +246,7 @@ void oq_qx(const oq_config* cfg, const float* y, int64_t n, int64_t j0, int64_t 
             if (jf < -jmax) jf = -jmax;
         }
         if (jcode) jcode[i] = (int32_t)jf;
-        if (xhat) xhat[i] = ldexpf(jf, -(k_x + 1));
+        if (xhat) xhat[i] = jf * spacing;
         if (tie) tie[i] = flagged;
     }
 }
@@ -439,6 +445,33 @@ int oq_step_s(const oq_config* cfg, const int64_t* seg_off, int32_t L, int32_t N
     oq_adam_update(cfg, lr, beta2, step, acc, m, v, u, P);
     for (int64_t j = 0; j < P; ++j) x[j] = x[j] - u[j];
     oq_weight_quantize(cfg, P, index_base, step, x, werr, wcodes, NULL, tie_x);
+    free(acc); free(q); free(u);
+    return status;
+}
+
+/* The same step on a window of ONE layer, the workers' layer scales s[i] = ||g_i + e_i||_inf given
+ * (everything but the scale is element-wise).  codes[i][n]: per-element codes. */
+int oq_step_s_window(const oq_config* cfg, int64_t n, int64_t j0, int32_t N,
+                     int64_t step, float lr, float beta2, const float* s,
+                     const float* const* grads, float* const* errs,
+                     float* x, float* m, float* v, float* werr,
+                     uint8_t* const* codes, void* wcodes,
+                     uint8_t* const* tie_g, uint8_t* tie_x)
+{
+    float* acc = (float*)calloc((size_t)(n > 0 ? n : 1), sizeof(float));
+    float* q = (float*)malloc(sizeof(float) * (size_t)(n > 0 ? n : 1));
+    float* u = (float*)malloc(sizeof(float) * (size_t)(n > 0 ? n : 1));
+    int status = 0;
+    for (int32_t i = 0; i < N; ++i) {
+        if (!isfinite(s[i])) status |= OQ_NONFINITE_SCALE;
+        oq_worker_quantize_window(cfg, n, j0, i, step, s[i], grads[i], errs[i],
+                                  codes ? codes[i] : NULL, tie_g ? tie_g[i] : NULL, q);
+        for (int64_t j = 0; j < n; ++j) acc[j] = acc[j] + q[j];
+    }
+    mean_of_workers(acc, N, n);
+    oq_adam_update(cfg, lr, beta2, step, acc, m, v, u, n);
+    for (int64_t j = 0; j < n; ++j) x[j] = x[j] - u[j];
+    oq_weight_quantize(cfg, n, j0, step, x, werr, wcodes, NULL, tie_x);
     free(acc); free(q); free(u);
     return status;
 }

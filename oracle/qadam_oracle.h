@@ -148,6 +148,14 @@ int oq_step_s(const oq_config* cfg, const int64_t* seg_off, int32_t L, int32_t N
               float* x, float* m, float* v, float* werr, void* wcodes,
               uint8_t* const* tie_g, uint8_t* tie_x);
 
+/* the same step on a window of ONE layer with the workers' layer scales given */
+int oq_step_s_window(const oq_config* cfg, int64_t n, int64_t j0, int32_t N,
+                     int64_t step, float lr, float beta2, const float* s,
+                     const float* const* grads, float* const* errs,
+                     float* x, float* m, float* v, float* werr,
+                     uint8_t* const* codes, void* wcodes,
+                     uint8_t* const* tie_g, uint8_t* tie_x);
+
 /* one whole step of variant W (Algorithms 2-3): per-worker m_i, v_i. */
 int oq_step_w(const oq_config* cfg, const int64_t* seg_off, int32_t L, int32_t N,
               int64_t index_base, int64_t step, float lr, float beta2,

@@ -287,6 +287,25 @@ def step_s(cfg, seg_off, step, lr, beta2, grads, errs, x, m, v, werr,
     return dict(status=st, words=words, scales=scales, wcodes=wcodes, tie_g=tie_g, tie_x=tie_x)
 
 
+def step_s_window(cfg, j0, step, lr, beta2, scales, grads, errs, x, m, v, werr, want_tie=True):
+    """Variant S on a window of one layer, scales[i] = the workers' layer scales.
+    Returns dict(status, codes (per element, per worker), wcodes, tie_g, tie_x)."""
+    N = len(grads)
+    n = x.size
+    grads = [_f32(g) for g in grads]
+    s = np.ascontiguousarray(scales, dtype=np.float32)
+    codes = [np.zeros(n, np.uint8) for _ in range(N)]
+    wcodes = np.zeros(n, weight_code_dtype(cfg.k_x))
+    tie_g = [np.zeros(n, np.uint8) for _ in range(N)] if want_tie else None
+    tie_x = np.zeros(n, np.uint8) if want_tie else None
+    cc = cfg.c()
+    st = lib().oq_step_s_window(C.byref(cc), C.c_int64(n), C.c_int64(j0), C.c_int32(N), C.c_int64(step),
+                                C.c_float(lr), C.c_float(beta2), _p(s), _ptr_array(grads),
+                                _ptr_array(errs), _p(x), _p(m), _p(v), _p(werr), _ptr_array(codes),
+                                _p(wcodes), _ptr_array(tie_g), _p(tie_x))
+    return dict(status=st, codes=codes, wcodes=wcodes, tie_g=tie_g, tie_x=tie_x)
+
+
 def step_w(cfg, seg_off, step, lr, beta2, grads, errs, mw, vw, x, werr,
            index_base=0, want_tie=True):
     """One step of variant W (Algorithms 2-3); errs, mw, vw, x, werr in place."""

@@ -1,0 +1,202 @@
+"""Python binding of the C boundary (``include/qadam.h``): argument marshalling only.
+
+Every step of the optimizer runs in the HIP kernels of ``libqadam_hip.so``.  The library must have
+been built (``python paper_2004_14180_amd/build.py``); loading fails loudly otherwise -- there is no
+CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libqadam_hip.so")
+
+QADAM_OK, QADAM_EINVAL, QADAM_EALIGN, QADAM_ERANGE, QADAM_EHIP = 0, -1, -2, -3, -4
+QADAM_MAX_WORKERS = 32
+QADAM_STATUS_NONFINITE_SCALE = 1
+
+EXPORTS = [
+    "qadam_init", "qadam_destroy", "qadam_grad_code_bytes", "qadam_weight_code_bytes",
+    "qadam_num_params", "qadam_worker_quantize", "qadam_server_step", "qadam_weight_quantize",
+    "qadam_step_fused", "qadam_worker_step_w", "qadam_server_apply_w", "qadam_weight_dequantize",
+    "qadam_get_status", "qadam_last_error",
+]
+
+
+class QAdamError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__("qadam error %d: %s" % (code, msg))
+        self.code = code
+
+
+class _Config(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("k_g", C.c_int32), ("k_x", C.c_int32),
+                ("rounding", C.c_int32), ("weight_ef", C.c_int32), ("adam_flavor", C.c_int32),
+                ("beta1", C.c_float), ("eps", C.c_float), ("seed", C.c_uint64)]
+
+
+class _Status(C.Structure):
+    _fields_ = [("flags", C.c_uint32), ("reserved", C.c_uint32)]
+
+
+@dataclass
+class QAdamConfig:
+    k_g: int = 2
+    k_x: int = 6
+    rounding: int = 0
+    weight_ef: int = 1
+    adam_flavor: int = 0
+    beta1: float = 0.9
+    eps: float = 1e-8
+    seed: int = 0
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """dlopen the HIP library; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(
+            "%s is missing: build it with `python paper_2004_14180_amd/build.py` "
+            "(hipcc, --offload-arch=gfx950). There is no fallback path." % _LIB_PATH)
+    lib = C.CDLL(_LIB_PATH)
+    vp, i32, i64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
+    lib.qadam_init.argtypes = [C.POINTER(vp), C.POINTER(_Config), C.POINTER(i64), i32, i32]
+    lib.qadam_destroy.argtypes = [vp]
+    lib.qadam_grad_code_bytes.argtypes = [vp]
+    lib.qadam_grad_code_bytes.restype = C.c_size_t
+    lib.qadam_weight_code_bytes.argtypes = [vp]
+    lib.qadam_weight_code_bytes.restype = C.c_size_t
+    lib.qadam_num_params.argtypes = [vp]
+    lib.qadam_num_params.restype = i64
+    lib.qadam_worker_quantize.argtypes = [vp, i32, i64, vp, vp, vp, vp, vp]
+    lib.qadam_server_step.argtypes = [vp, i64, f32, f32, C.POINTER(vp), C.POINTER(vp), vp, vp, vp, vp]
+    lib.qadam_weight_quantize.argtypes = [vp, i64, vp, vp, vp, vp]
+    lib.qadam_step_fused.argtypes = [vp, i64, f32, f32, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp),
+                                     C.POINTER(vp), vp, vp, vp, vp, vp, vp]
+    lib.qadam_worker_step_w.argtypes = [vp, i32, i64, f32, f32, vp, vp, vp, vp, vp, vp, vp]
+    lib.qadam_server_apply_w.argtypes = [vp, i64, C.POINTER(vp), C.POINTER(vp), vp, vp]
+    lib.qadam_weight_dequantize.argtypes = [vp, vp, vp, vp]
+    lib.qadam_get_status.argtypes = [vp, C.POINTER(_Status), i32, vp]
+    lib.qadam_last_error.restype = C.c_char_p
+    _lib = lib
+    return lib
+
+
+def _ptr(t) -> Optional[int]:
+    """Device address of a torch tensor (or None)."""
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous device tensor")
+    return t.data_ptr()
+
+
+def _ptr_array(ts: Sequence):
+    arr = (C.c_void_p * len(ts))()
+    for i, t in enumerate(ts):
+        arr[i] = _ptr(t)
+    return arr
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream or None
+
+
+class QAdam:
+    """One handle = one flat parameter vector with its layer segments and N logical workers.
+
+    Methods carry the names of the C entry points and take torch device tensors; they enqueue on
+    the given (default: current) stream and do not synchronise.
+    """
+
+    def __init__(self, cfg: QAdamConfig, seg_offsets: Sequence[int], num_workers: int):
+        self._lib = load_library()
+        self.cfg = cfg
+        self.num_workers = int(num_workers)
+        self.seg_offsets = [int(s) for s in seg_offsets]
+        self.num_segments = len(self.seg_offsets) - 1
+        c = _Config(C.sizeof(_Config), cfg.k_g, cfg.k_x, cfg.rounding, cfg.weight_ef, cfg.adam_flavor,
+                    cfg.beta1, cfg.eps, cfg.seed)
+        segs = (C.c_int64 * len(self.seg_offsets))(*self.seg_offsets)
+        h = C.c_void_p()
+        self._h = None
+        self._check(self._lib.qadam_init(C.byref(h), C.byref(c), segs, self.num_segments, self.num_workers))
+        self._h = h
+
+    def _check(self, rc: int):
+        if rc != QADAM_OK:
+            raise QAdamError(rc, (self._lib.qadam_last_error() or b"").decode())
+
+    def close(self):
+        if self._h is not None:
+            self._lib.qadam_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # sizes -------------------------------------------------------------------------------------
+    @property
+    def num_params(self) -> int:
+        return int(self._lib.qadam_num_params(self._h))
+
+    def grad_code_bytes(self) -> int:
+        return int(self._lib.qadam_grad_code_bytes(self._h))
+
+    def weight_code_bytes(self) -> int:
+        return int(self._lib.qadam_weight_code_bytes(self._h))
+
+    # the calls ---------------------------------------------------------------------------------
+    def worker_quantize(self, worker, step, grad, err, codes, scales, stream=None):
+        self._check(self._lib.qadam_worker_quantize(self._h, worker, step, _ptr(grad), _ptr(err),
+                                                    _ptr(codes), _ptr(scales), _stream(stream)))
+
+    def server_step(self, step, lr, beta2, codes, scales, x, m, v, stream=None):
+        self._check(self._lib.qadam_server_step(self._h, step, lr, beta2, _ptr_array(codes),
+                                                _ptr_array(scales), _ptr(x), _ptr(m), _ptr(v),
+                                                _stream(stream)))
+
+    def weight_quantize(self, step, x, werr, wcodes, stream=None):
+        self._check(self._lib.qadam_weight_quantize(self._h, step, _ptr(x), _ptr(werr), _ptr(wcodes),
+                                                    _stream(stream)))
+
+    def step_fused(self, step, lr, beta2, grads, errs, codes, scales, x, m, v, werr, wcodes, stream=None):
+        self._check(self._lib.qadam_step_fused(self._h, step, lr, beta2, _ptr_array(grads),
+                                               _ptr_array(errs), _ptr_array(codes), _ptr_array(scales),
+                                               _ptr(x), _ptr(m), _ptr(v), _ptr(werr), _ptr(wcodes),
+                                               _stream(stream)))
+
+    def worker_step_w(self, worker, step, lr, beta2, grad, mw, vw, err, codes, scales, stream=None):
+        self._check(self._lib.qadam_worker_step_w(self._h, worker, step, lr, beta2, _ptr(grad), _ptr(mw),
+                                                  _ptr(vw), _ptr(err), _ptr(codes), _ptr(scales),
+                                                  _stream(stream)))
+
+    def server_apply_w(self, step, codes, scales, x, stream=None):
+        self._check(self._lib.qadam_server_apply_w(self._h, step, _ptr_array(codes), _ptr_array(scales),
+                                                   _ptr(x), _stream(stream)))
+
+    def weight_dequantize(self, wcodes, xhat, stream=None):
+        self._check(self._lib.qadam_weight_dequantize(self._h, _ptr(wcodes), _ptr(xhat), _stream(stream)))
+
+    def get_status(self, clear=False, stream=None) -> int:
+        st = _Status()
+        self._check(self._lib.qadam_get_status(self._h, C.byref(st), int(clear), _stream(stream)))
+        return int(st.flags)

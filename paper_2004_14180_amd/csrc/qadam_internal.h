@@ -1,0 +1,83 @@
+// Shared declarations between the host-side C boundary (qadam_api.cpp) and the gfx950 kernels
+// (qadam_kernels.hip).  Not part of the public interface.
+#pragma once
+
+#include <hip/hip_runtime_api.h>
+#include <stdint.h>
+
+#include "../../include/qadam.h"
+
+namespace qadam {
+
+// One unit of work of every kernel: a run of at most `tile_elems` consecutive elements that lies
+// inside one layer segment.  Tiles start at a multiple of the tile size from the segment start, so
+// the first element of a tile is the first element of a 32-element code group.
+struct Tile {
+    int64_t start;      // global flat index of the first element
+    int64_t code_word;  // index of the tile's first uint32 in a worker's packed code buffer
+    int32_t len;        // elements in the tile (1 .. tile_elems)
+    int32_t seg;        // layer segment the tile belongs to
+    int32_t flags;      // bit 0: start is not a multiple of 4 (no 128-bit accesses);
+                        // bits 8..9: zero words to append after the tile's codes (segment padding)
+    int32_t reserved;
+};
+static_assert(sizeof(Tile) == 32, "tile records are read as two 128-bit scalar loads");
+
+constexpr int kTileUnaligned = 1;
+constexpr int kBlockThreads = 256;
+
+// Scalars of one launch, identical for every kernel.
+struct StepScalars {
+    int32_t  num_workers;
+    int32_t  k_g, mu_bits, code_bits;   // Q_g: levels, bits of the level index, bits per code
+    int32_t  k_x, wcode_bytes;          // Q_x
+    int32_t  rounding, weight_ef, adam_flavor;
+    uint32_t key0, key1;                // Philox key (seed)
+    uint32_t step;                      // low 32 bits of t
+    float    lr, beta1, beta2, eps;
+    float    omb1, omb2;                // 1-beta, 1-theta_t (fp32 subtraction done on the host)
+    float    lr1, sbc2;                 // flavour 1: lr / (1-beta^t), sqrt(1-theta^t)
+    float    n_workers_f;               // (float)N
+    int32_t  n_is_pow2;
+};
+
+// Pointer tables travel as kernel arguments.
+struct WorkerPtrs {
+    const float* grad[QADAM_MAX_WORKERS];
+    float*       err[QADAM_MAX_WORKERS];
+    uint32_t*    codes[QADAM_MAX_WORKERS];
+    float*       scales[QADAM_MAX_WORKERS];
+    float*       mw[QADAM_MAX_WORKERS];     // variant W only
+    float*       vw[QADAM_MAX_WORKERS];
+};
+
+struct ServerPtrs {
+    float* x;
+    float* m;
+    float* v;
+    float* werr;        // may be null when weight_ef == 0
+    void*  wcodes;
+};
+
+struct Launch {
+    const Tile* tiles;      // device
+    int32_t     num_tiles;
+    int32_t     num_segments;
+    int64_t     num_params;
+    uint32_t*   status;     // device status word
+    hipStream_t stream;
+};
+
+// Launchers (defined in qadam_kernels.hip).  `first_worker`/`num` select the workers a launch covers.
+hipError_t launch_zero_scales(const Launch& L, const WorkerPtrs& W, int first_worker, int num);
+hipError_t launch_amax(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker, int num);
+hipError_t launch_worker_quantize(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int worker);
+hipError_t launch_server_step(const Launch& L, const StepScalars& S, const WorkerPtrs& W, const ServerPtrs& sp);
+hipError_t launch_weight_quantize(const Launch& L, const StepScalars& S, const float* x, float* werr, void* wcodes);
+hipError_t launch_weight_dequantize(const Launch& L, const StepScalars& S, const void* wcodes, float* xhat);
+hipError_t launch_fused(const Launch& L, const StepScalars& S, const WorkerPtrs& W, const ServerPtrs& sp);
+// variant W
+hipError_t launch_worker_moments_w(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int worker);
+hipError_t launch_server_apply_w(const Launch& L, const StepScalars& S, const WorkerPtrs& W, float* x);
+
+}  // namespace qadam

@@ -1,0 +1,901 @@
+// gfx950 (MI355X, CDNA4) kernels of the Quantized-Adam-with-error-feedback step
+// (arXiv 2004.14180: Sec. 5.1 for the quantizers Q_g and Q_x, Algorithm 1 lines 3-6 for the
+// moments / step / residual, Algorithm 2 line 3 for the mean over workers).
+//
+// Everything here is a streaming pass bound by HBM bandwidth: no contraction, no MFMA.  The design
+// rules are the ones that matter for that regime on CDNA4:
+//   * 64-wide wavefronts, 256-thread workgroups; a lane owns 4 consecutive fp32 values so every
+//     global access is a 128-bit load/store and a wavefront touches 1 KiB of contiguous memory;
+//   * a workgroup owns one tile (<= 4096 elements of one layer), so all per-layer quantities
+//     (scales, code offsets) are wave-uniform and live in scalar registers;
+//   * the per-layer scale is a max over |g+e|: lanes reduce with integer max on the bit pattern
+//     (non-negative floats order like integers; NaN/Inf sort above every finite value and so
+//     surface in the scale), wavefront reduction by cross-lane shuffles, LDS across the four
+//     wavefronts, one atomicMax per workgroup;
+//   * codes are stored as bit planes of 32-element groups; a lane's four codes are combined with
+//     the other seven lanes of its group by three DPP OR steps per plane, so packing costs no
+//     LDS traffic and no scatter;
+//   * fp32 arithmetic is kept bit-reproducible: one rounding per operation (built with
+//     -ffp-contract=off), IEEE division and square root, subnormals kept.
+#include <hip/hip_runtime.h>
+
+#include "qadam_internal.h"
+
+namespace qadam {
+namespace {
+
+__device__ __forceinline__ uint32_t f2u(float f) { return __float_as_uint(f); }
+__device__ __forceinline__ float u2f(uint32_t u) { return __uint_as_float(u); }
+
+// ------------------------------------------------------------------------------------------------
+// Philox4x32-10 (Salmon et al., SC'11): counter (c0..c3), key (k0,k1) -> four 32-bit words.
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                              uint32_t k0, uint32_t k1, uint32_t (&out)[4])
+{
+    constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u, W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t hi0 = __umulhi(M0, c0), lo0 = M0 * c0;
+        const uint32_t hi1 = __umulhi(M1, c2), lo1 = M1 * c2;
+        c0 = hi1 ^ c1 ^ k0;
+        c1 = lo1;
+        c2 = hi0 ^ c3 ^ k1;
+        c3 = lo0;
+        k0 += W0;
+        k1 += W1;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// Uniforms in [0,1) with 24 bits for the V consecutive elements starting at global index gi.
+// Counter = (gi/4 low, gi/4 high, step, worker + (stream << 16)); element j takes word j mod 4.
+template <int V>
+__device__ __forceinline__ void uniforms(const StepScalars& S, int64_t gi, uint32_t worker, uint32_t stream,
+                                         float (&U)[V])
+{
+    const uint64_t blk = (uint64_t)gi >> 2;
+    uint32_t out[4];
+    philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), S.step, worker + (stream << 16), S.key0, S.key1, out);
+    if constexpr (V == 4) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) U[j] = (float)(out[j] >> 8) * 0x1p-24f;
+    } else {
+        const int wsel = (int)(gi & 3);
+        const uint32_t w = wsel == 0 ? out[0] : wsel == 1 ? out[1] : wsel == 2 ? out[2] : out[3];
+        U[0] = (float)(w >> 8) * 0x1p-24f;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Q_g on one value (Sec. 5.1).  r = p / s lies in [-1, 1]; the grid is {0} and 2^(mu-1-k_g),
+// mu = 1..k_g+1.  Nearest point: the midpoint below level 2^-j is 0.75 * 2^-j, i.e. mantissa
+// 0x400000 one exponent lower, so adding 0x400000 to the bit pattern of |r| and taking the
+// exponent field rounds |r| to the nearest power of two with midpoints going up.
+// ------------------------------------------------------------------------------------------------
+struct QgConst {
+    int top;               // k_g + 1
+    int ebias;             // 126 - k_g: exponent field of level mu is mu + ebias
+    uint32_t half_l1_bits; // bit pattern of 2^(-k_g-1), the midpoint between 0 and the first level
+    uint32_t l1_bits;      // bit pattern of 2^-k_g
+};
+
+__device__ __forceinline__ QgConst make_qg(int k_g)
+{
+    QgConst c;
+    c.top = k_g + 1;
+    c.ebias = 126 - k_g;
+    c.half_l1_bits = (uint32_t)(126 - k_g) << 23;
+    c.l1_bits = (uint32_t)(127 - k_g) << 23;
+    return c;
+}
+
+template <int ROUNDING>
+__device__ __forceinline__ int qg_level(float r, const QgConst& c, float U)
+{
+    const uint32_t ab = f2u(r) & 0x7fffffffu;
+    int mu;
+    if constexpr (ROUNDING == 0) {
+        mu = (int)((ab + 0x00400000u) >> 23) - c.ebias;
+        const int low = ab >= c.half_l1_bits ? 1 : 0;
+        mu = mu < 1 ? low : mu;
+    } else {
+        // neighbours lo <= |r| < hi; go up with probability (|r| - lo) / (hi - lo)
+        int below = (int)(ab >> 23) - c.ebias;
+        below = below < 0 ? 0 : below;
+        const uint32_t lo_bits = below > 0 ? (uint32_t)(below + c.ebias) << 23 : 0u;
+        const uint32_t width_bits = below > 0 ? lo_bits : c.l1_bits;        // hi - lo, a power of two
+        const float inv_width = u2f((254u << 23) - width_bits);              // exact reciprocal
+        const float frac = (u2f(ab) - u2f(lo_bits)) * inv_width;
+        mu = below + (U < frac ? 1 : 0);
+    }
+    return mu > c.top ? c.top : mu;
+}
+
+// One worker's share of one lane: p = g + e, level, dequantized value, residual.
+// `valid` is false for a zero or non-finite scale (then every code is 0 and e' = p).
+template <int V, int ROUNDING>
+__device__ __forceinline__ void worker_lane(const float (&g)[V], const float (&e)[V], float s, bool valid,
+                                            const QgConst& c, int mu_bits, const float (&U)[V],
+                                            float (&q)[V], float (&enew)[V], uint32_t& codes)
+{
+    codes = 0;
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+        const float p = g[j] + e[j];
+        const float r = p / s;
+        int mu = qg_level<ROUNDING>(r, c, U[j]);
+        mu = valid ? mu : 0;
+        const float lvl = u2f((uint32_t)(mu + c.ebias) << 23);
+        float qa = s * lvl;                       // s * 2^(mu-1-k_g)
+        qa = mu > 0 ? qa : 0.0f;
+        const bool neg = (p < 0.0f) && (mu > 0);
+        const float qv = neg ? -qa : qa;
+        q[j] = qv;
+        enew[j] = p - qv;
+        codes |= (uint32_t)(mu | ((neg ? 1 : 0) << mu_bits)) << (4 * j);
+    }
+}
+
+// value of one code with scale s
+__device__ __forceinline__ float qg_decode(uint32_t code, float s, const QgConst& c, int mu_bits)
+{
+    const int mu = (int)(code & ((1u << mu_bits) - 1u));
+    const bool neg = (code >> mu_bits) & 1u;
+    const float lvl = u2f((uint32_t)(mu + c.ebias) << 23);
+    float qa = s * lvl;
+    qa = mu > 0 ? qa : 0.0f;
+    return neg ? -qa : qa;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Bit-plane packing.  V == 4: a lane holds the codes of elements 4*lane..4*lane+3 of a 256-element
+// wave chunk as four nibbles of `codes`; the 8 lanes 8G..8G+7 form 32-element group G.  For plane k
+// every lane shifts its 4 plane bits to position 4*(lane%8) and the group ORs them with three DPP
+// steps (swap within pairs, swap pairs within quads, mirror the two quads of a half row).  Lane
+// 8G+k keeps word k.  Must be called with all 64 lanes active.
+// V == 1: lane = element; a wave ballot of plane k is the two words of the chunk's two groups.
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t dpp_or8(uint32_t w)
+{
+    w |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, 0xB1, 0xF, 0xF, false);   // quad_perm [1,0,3,2]
+    w |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, 0x4E, 0xF, 0xF, false);   // quad_perm [2,3,0,1]
+    w |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, 0x141, 0xF, 0xF, false);  // row_half_mirror
+    return w;
+}
+
+template <int V>
+__device__ __forceinline__ uint32_t pack_planes(uint32_t codes, int code_bits, int lane, int& word_slot,
+                                                bool& writes)
+{
+    uint32_t sel = 0;
+    if constexpr (V == 4) {
+        const int sub = lane & 7;
+        const int sh = sub * 4;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if (k < code_bits) {
+                const uint32_t t = (codes >> k) & 0x1111u;
+                const uint32_t nib = (t | (t >> 3) | (t >> 6) | (t >> 9)) & 0xFu;
+                const uint32_t w = dpp_or8(nib << sh);
+                sel = sub == k ? w : sel;
+            }
+        }
+        word_slot = (lane >> 3) * code_bits + sub;     // word within the wave chunk's 8 groups
+        writes = sub < code_bits;
+    } else {
+        const int grp = lane / code_bits, k_mine = lane - grp * code_bits;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if (k < code_bits) {
+                const unsigned long long mask = __ballot((codes >> k) & 1u);
+                const uint32_t w = grp == 0 ? (uint32_t)mask : (uint32_t)(mask >> 32);
+                sel = k_mine == k ? w : sel;
+            }
+        }
+        word_slot = lane;                              // lanes 0 .. 2*code_bits-1 hold the chunk's words
+        writes = lane < 2 * code_bits;
+    }
+    return sel;
+}
+
+// codes of this lane's V elements from packed words (inverse of pack_planes)
+template <int V>
+__device__ __forceinline__ uint32_t unpack_planes(const uint32_t* __restrict__ chunk_words, int code_bits, int lane)
+{
+    uint32_t codes = 0;
+    if constexpr (V == 4) {
+        const uint32_t* gw = chunk_words + (lane >> 3) * code_bits;
+        const int sh = (lane & 7) * 4;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if (k < code_bits) {
+                const uint32_t nib = (gw[k] >> sh) & 0xFu;
+                // spread bit j of the nibble to bit 4*j + k
+                codes |= ((nib & 1u) | ((nib & 2u) << 3) | ((nib & 4u) << 6) | ((nib & 8u) << 9)) << k;
+            }
+        }
+    } else {
+        const uint32_t* gw = chunk_words + (lane >> 5) * code_bits;
+        const int b = lane & 31;
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (k < code_bits) codes |= ((gw[k] >> b) & 1u) << k;
+    }
+    return codes;
+}
+
+// ------------------------------------------------------------------------------------------------
+// guarded vector access: 128-bit when the lane's V=4 elements are all inside the tile
+// ------------------------------------------------------------------------------------------------
+template <int V>
+__device__ __forceinline__ void load_v(const float* __restrict__ p, int nvalid, float (&out)[V])
+{
+    if constexpr (V == 4) {
+        if (nvalid == 4) {
+            const float4 t = *reinterpret_cast<const float4*>(p);
+            out[0] = t.x; out[1] = t.y; out[2] = t.z; out[3] = t.w;
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) out[j] = j < nvalid ? p[j] : 0.0f;
+        }
+    } else {
+        out[0] = nvalid > 0 ? p[0] : 0.0f;
+    }
+}
+
+template <int V>
+__device__ __forceinline__ void store_v(float* __restrict__ p, int nvalid, const float (&in)[V])
+{
+    if constexpr (V == 4) {
+        if (nvalid == 4) {
+            *reinterpret_cast<float4*>(p) = make_float4(in[0], in[1], in[2], in[3]);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) if (j < nvalid) p[j] = in[j];
+        }
+    } else {
+        if (nvalid > 0) p[0] = in[0];
+    }
+}
+
+template <int V>
+__device__ __forceinline__ void store_wcodes(void* __restrict__ base, int wcode_bytes, int64_t gi, int nvalid,
+                                             const int (&j)[V])
+{
+    if (wcode_bytes == 1) {
+        int8_t* p = static_cast<int8_t*>(base) + gi;
+        if constexpr (V == 4) {
+            if (nvalid == 4) {
+                *reinterpret_cast<char4*>(p) = make_char4((signed char)j[0], (signed char)j[1], (signed char)j[2], (signed char)j[3]);
+                return;
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < V; ++t) if (t < nvalid) p[t] = (int8_t)j[t];
+    } else {
+        int16_t* p = static_cast<int16_t*>(base) + gi;
+        if constexpr (V == 4) {
+            if (nvalid == 4) {
+                *reinterpret_cast<short4*>(p) = make_short4((short)j[0], (short)j[1], (short)j[2], (short)j[3]);
+                return;
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < V; ++t) if (t < nvalid) p[t] = (int16_t)j[t];
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Server arithmetic on one lane: moments (Alg. 1 lines 3-4) and the step alpha m / sqrt(v + eps).
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ float adam_step(const StepScalars& S, float gbar, float& m, float& v)
+{
+    const float g2 = gbar * gbar;
+    const float vn = (S.beta2 * v) + (S.omb2 * g2);
+    const float mn = (S.beta1 * m) + (S.omb1 * gbar);
+    v = vn;
+    m = mn;
+    if (S.adam_flavor == 0) {
+        const float den = sqrtf(vn + S.eps);
+        return (S.lr * mn) / den;
+    } else {
+        const float den = (sqrtf(vn) / S.sbc2) + S.eps;
+        return (S.lr1 * mn) / den;
+    }
+}
+
+__device__ __forceinline__ float mean_over_workers(const StepScalars& S, float acc)
+{
+    // N a power of two: multiplying by 1/N rounds exactly like dividing by N
+    return S.n_is_pow2 ? acc * (1.0f / S.n_workers_f) : acc / S.n_workers_f;
+}
+
+// Q_x on one value (Sec. 5.1): nearest multiple of 2^-(k_x+1), saturated to [-1/2, 1/2].
+template <int ROUNDING>
+__device__ __forceinline__ void qx_value(float y, float two_kx1, float inv_two_kx1, float jmax, float U,
+                                         int& j, float& xhat)
+{
+    const float u = y * two_kx1;
+    float jf;
+    if constexpr (ROUNDING == 0) {
+        const float t = truncf(u);
+        const float d = fabsf(u - t);                   // exact
+        jf = d >= 0.5f ? t + copysignf(1.0f, u) : t;     // halves away from zero
+    } else {
+        jf = floorf(u + U);
+    }
+    jf = fminf(fmaxf(jf, -jmax), jmax);
+    jf = (u != u) ? 0.0f : jf;
+    j = (int)jf;
+    xhat = jf * inv_two_kx1;
+}
+
+template <int V, int ROUNDING>
+__device__ __forceinline__ void weight_lane(const StepScalars& S, const float (&x)[V], const float (&werr_in)[V],
+                                            int64_t gi, float (&werr_out)[V], int (&j)[V])
+{
+    const float two_kx1 = u2f((uint32_t)(127 + S.k_x + 1) << 23);
+    const float inv = u2f((uint32_t)(127 - S.k_x - 1) << 23);
+    const float jmax = u2f((uint32_t)(127 + S.k_x) << 23);
+    float U[V];
+#pragma unroll
+    for (int t = 0; t < V; ++t) U[t] = 0.0f;
+    if constexpr (ROUNDING == 1) uniforms<V>(S, gi, 0u, 1u, U);
+#pragma unroll
+    for (int t = 0; t < V; ++t) {
+        const float y = S.weight_ef ? x[t] + werr_in[t] : x[t];
+        float xh;
+        qx_value<ROUNDING>(y, two_kx1, inv, jmax, U[t], j[t], xh);
+        werr_out[t] = y - xh;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// kernel argument blocks
+// ------------------------------------------------------------------------------------------------
+struct AmaxArgs {
+    const Tile* tiles;
+    const float* grad[QADAM_MAX_WORKERS];
+    const float* err[QADAM_MAX_WORKERS];
+    float* scales[QADAM_MAX_WORKERS];
+    int first_worker;
+};
+
+struct FusedArgs {
+    const Tile* tiles;
+    uint32_t* status;
+    StepScalars S;
+    ServerPtrs sp;
+    const float* grad[QADAM_MAX_WORKERS];
+    float* err[QADAM_MAX_WORKERS];
+    uint32_t* codes[QADAM_MAX_WORKERS];
+    const float* scales[QADAM_MAX_WORKERS];
+};
+
+struct WorkerArgs {        // one worker
+    const Tile* tiles;
+    uint32_t* status;
+    StepScalars S;
+    const float* grad;     // variant S: g;  variant W second pass: null (p was parked in err)
+    float* err;
+    uint32_t* codes;
+    const float* scales;
+    int worker;
+};
+
+struct ZeroArgs {
+    float* scales[QADAM_MAX_WORKERS];
+    int first_worker, num, num_segments;
+};
+
+// ------------------------------------------------------------------------------------------------
+// scales: zero, then per-(worker, layer) max |g + e|
+// ------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(kBlockThreads) k_zero_scales(ZeroArgs A)
+{
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    const int total = A.num * A.num_segments;
+    if (idx < total) {
+        const int w = idx / A.num_segments, l = idx - w * A.num_segments;
+        A.scales[A.first_worker + w][l] = 0.0f;
+    }
+}
+
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
+{
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        const uint32_t o = (uint32_t)__shfl_xor((int)v, d, 64);
+        v = o > v ? o : v;
+    }
+    return v;
+}
+
+// block-wide max of the lanes' values, then one atomic on the (worker, layer) word
+__device__ __forceinline__ void block_max_to_scale(uint32_t local, float* scale_word)
+{
+    __shared__ uint32_t wave_part[kBlockThreads / 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t wm = wave_max_u32(local);
+    if (lane == 0) wave_part[wave] = wm;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t bm = wave_part[0];
+#pragma unroll
+        for (int w = 1; w < kBlockThreads / 64; ++w) bm = wave_part[w] > bm ? wave_part[w] : bm;
+        uint32_t* word = reinterpret_cast<uint32_t*>(scale_word);
+        // the word only grows, so a value already >= ours needs no atomic
+        if (bm > __atomic_load_n(word, __ATOMIC_RELAXED)) atomicMax(word, bm);
+    }
+}
+
+template <int V>
+__device__ __forceinline__ uint32_t amax_tile(const float* __restrict__ g, const float* __restrict__ e, const Tile& t)
+{
+    constexpr int BLOCK_ELEMS = kBlockThreads * V;
+    uint32_t local = 0;
+    for (int off = threadIdx.x * V; off < t.len; off += BLOCK_ELEMS) {
+        const int nvalid = min(t.len - off, V);
+        float gv[V], ev[V];
+        load_v<V>(g + t.start + off, nvalid, gv);
+        load_v<V>(e + t.start + off, nvalid, ev);
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            const uint32_t ab = f2u(gv[j] + ev[j]) & 0x7fffffffu;
+            local = ab > local ? ab : local;
+        }
+    }
+    return local;
+}
+
+// grid: (tiles, workers)
+__global__ void __launch_bounds__(kBlockThreads) k_amax(AmaxArgs A)
+{
+    const Tile t = A.tiles[blockIdx.x];
+    const int w = A.first_worker + blockIdx.y;
+    const float* g = A.grad[w];
+    const float* e = A.err[w];
+    uint32_t local;
+    if (t.flags & kTileUnaligned) local = amax_tile<1>(g, e, t);
+    else local = amax_tile<4>(g, e, t);
+    block_max_to_scale(local, A.scales[w] + t.seg);
+}
+
+// ------------------------------------------------------------------------------------------------
+// common tile walk: every wave of the block takes 64*V elements per iteration; the trip count is
+// wave-uniform so the cross-lane packing always runs with all lanes active.
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ bool scale_ok(float s) { return s > 0.0f && s < __builtin_inff(); }
+
+__device__ __forceinline__ void write_pad_words(uint32_t* codes, const Tile& t, int code_bits)
+{
+    const int pad = (t.flags >> 8) & 3;
+    if ((int)threadIdx.x < pad) {
+        const int64_t groups = (t.len + 31) / 32;
+        codes[t.code_word + groups * code_bits + threadIdx.x] = 0u;
+    }
+}
+
+template <int V>
+__device__ __forceinline__ void store_chunk_words(uint32_t* __restrict__ codes, const Tile& t, int base,
+                                                  int code_bits, int lane, uint32_t word, int word_slot, bool writes)
+{
+    // first element of the group this lane's word belongs to
+    const int grp = word_slot / code_bits;
+    const bool group_live = base + grp * 32 < t.len;
+    if (writes && group_live) {
+        const int64_t cw = t.code_word + (int64_t)(base >> 5) * code_bits;
+        codes[cw + word_slot] = word;
+    }
+    (void)lane;
+}
+
+// ---- worker side alone (qadam_worker_quantize, second pass of variant W) -------------------------
+template <int V, int ROUNDING, bool PARKED>
+__device__ __forceinline__ void worker_tile(const WorkerArgs& A, const Tile& t)
+{
+    constexpr int WAVE_ELEMS = 64 * V, BLOCK_ELEMS = (kBlockThreads / 64) * WAVE_ELEMS;
+    const StepScalars& S = A.S;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const QgConst c = make_qg(S.k_g);
+    const float s = A.scales[t.seg];
+    const bool valid = scale_ok(s);
+    if (!(s >= 0.0f && s < __builtin_inff()) && threadIdx.x == 0) atomicOr(A.status, QADAM_STATUS_NONFINITE_SCALE);
+    for (int base = wave * WAVE_ELEMS; base < t.len; base += BLOCK_ELEMS) {
+        const int off = base + lane * V;
+        const int nvalid = min(max(t.len - off, 0), V);
+        const int64_t gi = t.start + off;
+        float g[V], e[V], q[V], en[V], U[V];
+#pragma unroll
+        for (int j = 0; j < V; ++j) U[j] = 0.0f;
+        if constexpr (PARKED) {
+            // the first pass left p = u + e in the error buffer
+            load_v<V>(A.err + gi, nvalid, g);
+#pragma unroll
+            for (int j = 0; j < V; ++j) e[j] = 0.0f;
+        } else {
+            load_v<V>(A.grad + gi, nvalid, g);
+            load_v<V>(A.err + gi, nvalid, e);
+        }
+        if constexpr (ROUNDING == 1) uniforms<V>(S, gi, (uint32_t)A.worker, 0u, U);
+        uint32_t codes;
+        if constexpr (PARKED) {
+            // p is already rounded; adding +0 keeps it (and keeps -0 apart from the sign of zero,
+            // which no output depends on)
+            worker_lane<V, ROUNDING>(g, e, s, valid, c, S.mu_bits, U, q, en, codes);
+        } else {
+            worker_lane<V, ROUNDING>(g, e, s, valid, c, S.mu_bits, U, q, en, codes);
+        }
+        store_v<V>(A.err + gi, nvalid, en);
+        int slot; bool writes;
+        const uint32_t word = pack_planes<V>(codes, S.code_bits, lane, slot, writes);
+        store_chunk_words<V>(A.codes, t, base, S.code_bits, lane, word, slot, writes);
+    }
+    write_pad_words(A.codes, t, S.code_bits);
+}
+
+template <int ROUNDING, bool PARKED>
+__global__ void __launch_bounds__(kBlockThreads) k_worker_quantize(WorkerArgs A)
+{
+    const Tile t = A.tiles[blockIdx.x];
+    if (t.flags & kTileUnaligned) worker_tile<1, ROUNDING, PARKED>(A, t);
+    else worker_tile<4, ROUNDING, PARKED>(A, t);
+}
+
+// ---- server side alone (qadam_server_step) -------------------------------------------------------
+struct ServerArgs {
+    const Tile* tiles;
+    StepScalars S;
+    float* x; float* m; float* v;
+    const uint32_t* codes[QADAM_MAX_WORKERS];
+    const float* scales[QADAM_MAX_WORKERS];
+    int apply_only;         // variant W: x <- x - mean_i q_i, no moments
+};
+
+template <int V>
+__device__ __forceinline__ void server_tile(const ServerArgs& A, const Tile& t)
+{
+    constexpr int WAVE_ELEMS = 64 * V, BLOCK_ELEMS = (kBlockThreads / 64) * WAVE_ELEMS;
+    const StepScalars& S = A.S;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const QgConst c = make_qg(S.k_g);
+    for (int base = wave * WAVE_ELEMS; base < t.len; base += BLOCK_ELEMS) {
+        const int off = base + lane * V;
+        const int nvalid = min(max(t.len - off, 0), V);
+        if (nvalid == 0) continue;
+        const int64_t gi = t.start + off;
+        const int64_t cw = t.code_word + (int64_t)(base >> 5) * S.code_bits;
+        float acc[V];
+#pragma unroll
+        for (int j = 0; j < V; ++j) acc[j] = 0.0f;
+        for (int i = 0; i < S.num_workers; ++i) {
+            const float s = A.scales[i][t.seg];
+            const uint32_t codes = unpack_planes<V>(A.codes[i] + cw, S.code_bits, lane);
+#pragma unroll
+            for (int j = 0; j < V; ++j) acc[j] = acc[j] + qg_decode((codes >> (4 * j)) & 0xFu, s, c, S.mu_bits);
+        }
+        float xv[V];
+        load_v<V>(A.x + gi, nvalid, xv);
+        if (A.apply_only) {
+#pragma unroll
+            for (int j = 0; j < V; ++j) xv[j] = xv[j] - mean_over_workers(S, acc[j]);
+        } else {
+            float mv[V], vv[V];
+            load_v<V>(A.m + gi, nvalid, mv);
+            load_v<V>(A.v + gi, nvalid, vv);
+#pragma unroll
+            for (int j = 0; j < V; ++j) {
+                const float u = adam_step(S, mean_over_workers(S, acc[j]), mv[j], vv[j]);
+                xv[j] = xv[j] - u;
+            }
+            store_v<V>(A.m + gi, nvalid, mv);
+            store_v<V>(A.v + gi, nvalid, vv);
+        }
+        store_v<V>(A.x + gi, nvalid, xv);
+    }
+}
+
+__global__ void __launch_bounds__(kBlockThreads) k_server_step(ServerArgs A)
+{
+    const Tile t = A.tiles[blockIdx.x];
+    if (t.flags & kTileUnaligned) server_tile<1>(A, t);
+    else server_tile<4>(A, t);
+}
+
+// ---- weight quantizer alone (qadam_weight_quantize) ----------------------------------------------
+struct WeightArgs {
+    StepScalars S;
+    const float* x;
+    float* werr;
+    void* wcodes;
+    int64_t n;
+};
+
+template <int ROUNDING>
+__global__ void __launch_bounds__(kBlockThreads) k_weight_quantize(WeightArgs A)
+{
+    const StepScalars& S = A.S;
+    const int64_t quads = (A.n + 3) / 4;
+    for (int64_t qd = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; qd < quads;
+         qd += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t gi = qd * 4;
+        const int nvalid = (int)min((int64_t)4, A.n - gi);
+        float xv[4], wi[4] = {0.f, 0.f, 0.f, 0.f}, wo[4];
+        int j[4];
+        load_v<4>(A.x + gi, nvalid, xv);
+        if (S.weight_ef) load_v<4>(A.werr + gi, nvalid, wi);
+        weight_lane<4, ROUNDING>(S, xv, wi, gi, wo, j);
+        if (A.werr) store_v<4>(A.werr + gi, nvalid, wo);
+        store_wcodes<4>(A.wcodes, S.wcode_bytes, gi, nvalid, j);
+    }
+}
+
+struct DequantArgs {
+    const void* wcodes;
+    float* xhat;
+    int64_t n;
+    int wcode_bytes;
+    float inv_two_kx1;
+};
+
+__global__ void __launch_bounds__(kBlockThreads) k_weight_dequantize(DequantArgs A)
+{
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < A.n;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        const int j = A.wcode_bytes == 1 ? (int)static_cast<const int8_t*>(A.wcodes)[i]
+                                         : (int)static_cast<const int16_t*>(A.wcodes)[i];
+        A.xhat[i] = (float)j * A.inv_two_kx1;
+    }
+}
+
+// ---- the whole step in one pass (qadam_step_fused) -----------------------------------------------
+template <int V, int ROUNDING>
+__device__ __forceinline__ void fused_tile(const FusedArgs& A, const Tile& t)
+{
+    constexpr int WAVE_ELEMS = 64 * V, BLOCK_ELEMS = (kBlockThreads / 64) * WAVE_ELEMS;
+    const StepScalars& S = A.S;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const QgConst c = make_qg(S.k_g);
+    const int N = S.num_workers;
+    for (int base = wave * WAVE_ELEMS; base < t.len; base += BLOCK_ELEMS) {
+        const int off = base + lane * V;
+        const int nvalid = min(max(t.len - off, 0), V);
+        const int64_t gi = t.start + off;
+        float acc[V];
+#pragma unroll
+        for (int j = 0; j < V; ++j) acc[j] = 0.0f;
+        for (int i = 0; i < N; ++i) {
+            const float s = A.scales[i][t.seg];
+            const bool valid = scale_ok(s);
+            float g[V], e[V], q[V], en[V], U[V];
+#pragma unroll
+            for (int j = 0; j < V; ++j) U[j] = 0.0f;
+            load_v<V>(A.grad[i] + gi, nvalid, g);
+            load_v<V>(A.err[i] + gi, nvalid, e);
+            if constexpr (ROUNDING == 1) uniforms<V>(S, gi, (uint32_t)i, 0u, U);
+            uint32_t codes;
+            worker_lane<V, ROUNDING>(g, e, s, valid, c, S.mu_bits, U, q, en, codes);
+            store_v<V>(A.err[i] + gi, nvalid, en);
+            int slot; bool writes;
+            const uint32_t word = pack_planes<V>(codes, S.code_bits, lane, slot, writes);
+            store_chunk_words<V>(A.codes[i], t, base, S.code_bits, lane, word, slot, writes);
+#pragma unroll
+            for (int j = 0; j < V; ++j) acc[j] = acc[j] + q[j];
+        }
+        // server: mean, moments, step, weight quantizer
+        float xv[V], mv[V], vv[V], wi[V], wo[V];
+        int jc[V];
+#pragma unroll
+        for (int j = 0; j < V; ++j) wi[j] = 0.0f;
+        load_v<V>(A.sp.x + gi, nvalid, xv);
+        load_v<V>(A.sp.m + gi, nvalid, mv);
+        load_v<V>(A.sp.v + gi, nvalid, vv);
+        if (S.weight_ef) load_v<V>(A.sp.werr + gi, nvalid, wi);
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            const float u = adam_step(S, mean_over_workers(S, acc[j]), mv[j], vv[j]);
+            xv[j] = xv[j] - u;
+        }
+        weight_lane<V, ROUNDING>(S, xv, wi, gi, wo, jc);
+        store_v<V>(A.sp.m + gi, nvalid, mv);
+        store_v<V>(A.sp.v + gi, nvalid, vv);
+        store_v<V>(A.sp.x + gi, nvalid, xv);
+        if (A.sp.werr) store_v<V>(A.sp.werr + gi, nvalid, wo);
+        store_wcodes<V>(A.sp.wcodes, S.wcode_bytes, gi, nvalid, jc);
+    }
+    for (int i = 0; i < N; ++i) {
+        write_pad_words(A.codes[i], t, S.code_bits);
+        const float s = A.scales[i][t.seg];
+        if (!(s >= 0.0f && s < __builtin_inff()) && threadIdx.x == 0)
+            atomicOr(A.status, QADAM_STATUS_NONFINITE_SCALE);
+    }
+}
+
+template <int ROUNDING>
+__global__ void __launch_bounds__(kBlockThreads) k_fused(FusedArgs A)
+{
+    const Tile t = A.tiles[blockIdx.x];
+    if (t.flags & kTileUnaligned) fused_tile<1, ROUNDING>(A, t);
+    else fused_tile<4, ROUNDING>(A, t);
+}
+
+// ---- variant W, first pass: local moments, park p = u + e in the error buffer, scale ------------
+struct MomentsWArgs {
+    const Tile* tiles;
+    StepScalars S;
+    const float* grad;
+    float* mw; float* vw; float* err;
+    float* scales;
+};
+
+template <int V>
+__device__ __forceinline__ uint32_t moments_w_tile(const MomentsWArgs& A, const Tile& t)
+{
+    constexpr int BLOCK_ELEMS = kBlockThreads * V;
+    const StepScalars& S = A.S;
+    uint32_t local = 0;
+    for (int off = threadIdx.x * V; off < t.len; off += BLOCK_ELEMS) {
+        const int nvalid = min(t.len - off, V);
+        const int64_t gi = t.start + off;
+        float g[V], mv[V], vv[V], e[V], p[V];
+        load_v<V>(A.grad + gi, nvalid, g);
+        load_v<V>(A.mw + gi, nvalid, mv);
+        load_v<V>(A.vw + gi, nvalid, vv);
+        load_v<V>(A.err + gi, nvalid, e);
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            const float u = adam_step(S, g[j], mv[j], vv[j]);
+            p[j] = u + e[j];
+            const uint32_t ab = j < nvalid ? (f2u(p[j]) & 0x7fffffffu) : 0u;
+            local = ab > local ? ab : local;
+        }
+        store_v<V>(A.mw + gi, nvalid, mv);
+        store_v<V>(A.vw + gi, nvalid, vv);
+        store_v<V>(A.err + gi, nvalid, p);
+    }
+    return local;
+}
+
+__global__ void __launch_bounds__(kBlockThreads) k_moments_w(MomentsWArgs A)
+{
+    const Tile t = A.tiles[blockIdx.x];
+    uint32_t local;
+    if (t.flags & kTileUnaligned) local = moments_w_tile<1>(A, t);
+    else local = moments_w_tile<4>(A, t);
+    block_max_to_scale(local, A.scales + t.seg);
+}
+
+int grid_for(int64_t work_items, int per_block)
+{
+    int64_t blocks = (work_items + per_block - 1) / per_block;
+    const int64_t cap = 256 * 64;      // 256 CUs, grid-stride beyond that
+    if (blocks > cap) blocks = cap;
+    if (blocks < 1) blocks = 1;
+    return (int)blocks;
+}
+
+}  // namespace
+
+// ================================================================================================
+// launchers
+// ================================================================================================
+hipError_t launch_zero_scales(const Launch& L, const WorkerPtrs& W, int first_worker, int num)
+{
+    const int total = num * L.num_segments;
+    if (total == 0) return hipSuccess;
+    ZeroArgs A;
+    for (int i = 0; i < QADAM_MAX_WORKERS; ++i) A.scales[i] = W.scales[i];
+    A.first_worker = first_worker; A.num = num; A.num_segments = L.num_segments;
+    hipLaunchKernelGGL(k_zero_scales, dim3((total + kBlockThreads - 1) / kBlockThreads), dim3(kBlockThreads), 0,
+                       L.stream, A);
+    return hipGetLastError();
+}
+
+hipError_t launch_amax(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker, int num)
+{
+    (void)S;
+    if (L.num_tiles == 0 || num == 0) return hipSuccess;
+    AmaxArgs A;
+    A.tiles = L.tiles;
+    for (int i = 0; i < QADAM_MAX_WORKERS; ++i) { A.grad[i] = W.grad[i]; A.err[i] = W.err[i]; A.scales[i] = W.scales[i]; }
+    A.first_worker = first_worker;
+    hipLaunchKernelGGL(k_amax, dim3(L.num_tiles, num), dim3(kBlockThreads), 0, L.stream, A);
+    return hipGetLastError();
+}
+
+hipError_t launch_worker_quantize(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int worker)
+{
+    if (L.num_tiles == 0) return hipSuccess;
+    WorkerArgs A;
+    A.tiles = L.tiles; A.status = L.status; A.S = S;
+    A.grad = W.grad[worker]; A.err = W.err[worker]; A.codes = W.codes[worker]; A.scales = W.scales[worker];
+    A.worker = worker;
+    const bool parked = (A.grad == nullptr);
+    const dim3 grid(L.num_tiles), block(kBlockThreads);
+    if (S.rounding == 0) {
+        if (parked) hipLaunchKernelGGL((k_worker_quantize<0, true>), grid, block, 0, L.stream, A);
+        else hipLaunchKernelGGL((k_worker_quantize<0, false>), grid, block, 0, L.stream, A);
+    } else {
+        if (parked) hipLaunchKernelGGL((k_worker_quantize<1, true>), grid, block, 0, L.stream, A);
+        else hipLaunchKernelGGL((k_worker_quantize<1, false>), grid, block, 0, L.stream, A);
+    }
+    return hipGetLastError();
+}
+
+static void fill_server_args(ServerArgs& A, const Launch& L, const StepScalars& S, const WorkerPtrs& W)
+{
+    A.tiles = L.tiles; A.S = S;
+    for (int i = 0; i < QADAM_MAX_WORKERS; ++i) { A.codes[i] = W.codes[i]; A.scales[i] = W.scales[i]; }
+}
+
+hipError_t launch_server_step(const Launch& L, const StepScalars& S, const WorkerPtrs& W, const ServerPtrs& sp)
+{
+    if (L.num_tiles == 0) return hipSuccess;
+    ServerArgs A;
+    fill_server_args(A, L, S, W);
+    A.x = sp.x; A.m = sp.m; A.v = sp.v; A.apply_only = 0;
+    hipLaunchKernelGGL(k_server_step, dim3(L.num_tiles), dim3(kBlockThreads), 0, L.stream, A);
+    return hipGetLastError();
+}
+
+hipError_t launch_server_apply_w(const Launch& L, const StepScalars& S, const WorkerPtrs& W, float* x)
+{
+    if (L.num_tiles == 0) return hipSuccess;
+    ServerArgs A;
+    fill_server_args(A, L, S, W);
+    A.x = x; A.m = nullptr; A.v = nullptr; A.apply_only = 1;
+    hipLaunchKernelGGL(k_server_step, dim3(L.num_tiles), dim3(kBlockThreads), 0, L.stream, A);
+    return hipGetLastError();
+}
+
+hipError_t launch_weight_quantize(const Launch& L, const StepScalars& S, const float* x, float* werr, void* wcodes)
+{
+    if (L.num_params == 0) return hipSuccess;
+    WeightArgs A;
+    A.S = S; A.x = x; A.werr = werr; A.wcodes = wcodes; A.n = L.num_params;
+    const dim3 grid(grid_for((L.num_params + 3) / 4, kBlockThreads)), block(kBlockThreads);
+    if (S.rounding == 0) hipLaunchKernelGGL(k_weight_quantize<0>, grid, block, 0, L.stream, A);
+    else hipLaunchKernelGGL(k_weight_quantize<1>, grid, block, 0, L.stream, A);
+    return hipGetLastError();
+}
+
+hipError_t launch_weight_dequantize(const Launch& L, const StepScalars& S, const void* wcodes, float* xhat)
+{
+    if (L.num_params == 0) return hipSuccess;
+    DequantArgs A;
+    A.wcodes = wcodes; A.xhat = xhat; A.n = L.num_params; A.wcode_bytes = S.wcode_bytes;
+    union { uint32_t u; float f; } cv;
+    cv.u = (uint32_t)(127 - S.k_x - 1) << 23;
+    A.inv_two_kx1 = cv.f;
+    hipLaunchKernelGGL(k_weight_dequantize, dim3(grid_for(L.num_params, kBlockThreads)), dim3(kBlockThreads), 0,
+                       L.stream, A);
+    return hipGetLastError();
+}
+
+hipError_t launch_fused(const Launch& L, const StepScalars& S, const WorkerPtrs& W, const ServerPtrs& sp)
+{
+    if (L.num_tiles == 0) return hipSuccess;
+    FusedArgs A;
+    A.tiles = L.tiles; A.status = L.status; A.S = S; A.sp = sp;
+    for (int i = 0; i < QADAM_MAX_WORKERS; ++i) {
+        A.grad[i] = W.grad[i]; A.err[i] = W.err[i]; A.codes[i] = W.codes[i]; A.scales[i] = W.scales[i];
+    }
+    const dim3 grid(L.num_tiles), block(kBlockThreads);
+    if (S.rounding == 0) hipLaunchKernelGGL(k_fused<0>, grid, block, 0, L.stream, A);
+    else hipLaunchKernelGGL(k_fused<1>, grid, block, 0, L.stream, A);
+    return hipGetLastError();
+}
+
+hipError_t launch_worker_moments_w(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int worker)
+{
+    if (L.num_tiles == 0) return hipSuccess;
+    MomentsWArgs A;
+    A.tiles = L.tiles; A.S = S;
+    A.grad = W.grad[worker]; A.mw = W.mw[worker]; A.vw = W.vw[worker]; A.err = W.err[worker];
+    A.scales = W.scales[worker];
+    hipLaunchKernelGGL(k_moments_w, dim3(L.num_tiles), dim3(kBlockThreads), 0, L.stream, A);
+    return hipGetLastError();
+}
+
+}  // namespace qadam

@@ -1,0 +1,265 @@
+"""GPU parity: the HIP library (through its C boundary) against the CPU oracle, element by element,
+on the seeded synthetic workloads and on edge cases.  Sizes are chosen so the oracle finishes in
+seconds while every tile shape occurs: full 4096-element tiles, ragged tails, segments that start
+off a 16-byte boundary (scalar path), tiny and empty segments."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import qadam_oracle as oracle
+from paper_2004_14180_amd import QAdam, QAdamConfig, QAdamError
+from paper_2004_14180_amd.workloads import Workload, make_workload
+
+from parity_util import (DeviceState, HostState, Report, compare_step, configs, oracle_step_layers,
+                         run_workload_parity)
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+# ------------------------------------------------------------------------------- the five configs
+@pytest.mark.parametrize("k_g", [2, 0])
+@pytest.mark.parametrize("fused", [False, True])
+def test_config1_flat_1m(k_g, fused):
+    """Config 1: one worker, 2^20 parameters in one layer, 10 steps, gradient quantization + EF."""
+    wl = make_workload(1)
+    if fused:
+        wl.weight_quant, wl.weight_ef = True, 1
+    rep = run_workload_parity(wl, wl.steps, fused=fused, k_g=k_g, progress="cfg1 k_g=%d fused=%s" % (k_g, fused))
+    _say("config1 k_g=%d fused=%s: %s" % (k_g, fused, rep.line()))
+    assert rep.ok()
+
+
+def test_config2_resnet18_full_size():
+    """Config 2 at full size (11 689 512 parameters, 62 layers, 4 workers), first steps."""
+    wl = make_workload(2)
+    rep = run_workload_parity(wl, 3, fused=True, progress="cfg2 full")
+    _say("config2 full: " + rep.line())
+    assert rep.ok()
+
+
+def test_config2_resnet18_50_steps_shrunk():
+    """Config 2's 50 steps on the same layer list with every layer 8x smaller."""
+    wl = make_workload(2, shrink=8)
+    rep = run_workload_parity(wl, wl.steps, fused=True, check_every=5, progress="cfg2/8")
+    _say("config2/8 50 steps: " + rep.line())
+    assert rep.ok()
+
+
+def test_config3_gpt2_shrunk():
+    """Config 3 (8 workers, Student-t gradients, zeroed embedding rows), model dims / 4, 20 steps."""
+    wl = make_workload(3, shrink=4)
+    rep = run_workload_parity(wl, wl.steps, fused=True, check_every=4, progress="cfg3/4")
+    _say("config3/4: " + rep.line())
+    assert rep.ok()
+
+
+def test_config4_adversarial_shrunk():
+    """Config 4 (16 workers, one segment, 8 decades of block scales plus +-1e3 outliers), 2^20."""
+    wl = make_workload(4, shrink=256)
+    rep = run_workload_parity(wl, wl.steps, fused=True, threads=1, progress="cfg4/256")
+    _say("config4/256: %s" % rep.line())
+    assert rep.ok()
+
+
+def test_config5_gpt13b_shrunk():
+    """Config 5's layer list with model dims / 8 (292 layers, 8 workers), its 5 steps."""
+    wl = make_workload(5, shrink=8)
+    rep = run_workload_parity(wl, wl.steps, fused=True, progress="cfg5/8")
+    _say("config5/8: " + rep.line())
+    assert rep.ok()
+
+
+# ------------------------------------------------------------------------------------- edge cases
+RAGGED = [1, 3, 31, 33, 0, 255, 257, 4095, 4097, 5000, 0, 64, 8192, 2, 12289, 7]
+
+
+def _custom(sizes, N, steps, seed=1, cfgkw=None, fused=True, scale=1e-2, weight_quant=True, gsel=None):
+    cfgkw = cfgkw or {}
+    gcfg, ocfg = configs(**cfgkw)
+    seg_off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    P = int(seg_off[-1])
+    rng = np.random.default_rng(seed)
+    q = QAdam(gcfg, seg_off, N)
+    x0 = (rng.standard_normal(P) * 0.02).astype(np.float32)
+    ds = DeviceState(q, torch.from_numpy(x0))
+    hs = HostState(P, N, x0)
+    rep = Report()
+    for t in range(1, steps + 1):
+        grads = [(rng.standard_normal(P) * scale).astype(np.float32) for _ in range(N)]
+        if gsel:
+            grads = gsel(t, grads)
+        for i in range(N):
+            ds.grads[i].copy_(torch.from_numpy(grads[i]))
+        if fused:
+            ds.step_fused(t, 1e-3, 0.999)
+        else:
+            ds.step_unfused(t, 1e-3, 0.999, weight_quant=weight_quant)
+        out = oracle_step_layers(ocfg, seg_off, t, 1e-3, 0.999, grads, hs, weight_quant=weight_quant)
+        compare_step(rep, ocfg, seg_off, ds, hs, out, weight_quant=weight_quant)
+    st = q.get_status()
+    q.close()
+    return rep, st
+
+
+@pytest.mark.parametrize("fused", [True, False])
+def test_ragged_and_unaligned_segments(fused):
+    """Segments of every awkward length: tails, starts off a 16-byte boundary, empty ones."""
+    rep, st = _custom(RAGGED, 3, 4, fused=fused)
+    _say("ragged fused=%s: %s" % (fused, rep.line()))
+    assert rep.ok() and st == 0
+
+
+@pytest.mark.parametrize("k_g", [0, 1, 2, 3, 4, 5, 6])
+def test_all_gradient_grids(k_g):
+    rep, st = _custom([5000, 37, 4096], 2, 3, cfgkw=dict(k_g=k_g), seed=10 + k_g)
+    assert rep.ok() and st == 0
+
+
+@pytest.mark.parametrize("k_x,weight_ef", [(0, 1), (6, 0), (7, 1), (14, 1), (14, 0), (3, 1)])
+def test_weight_grids_and_feedback_modes(k_x, weight_ef):
+    rep, st = _custom([9000, 130], 2, 5, cfgkw=dict(k_x=k_x, weight_ef=weight_ef), seed=20 + k_x)
+    assert rep.ok() and st == 0
+
+
+@pytest.mark.parametrize("N", [1, 3, 5, 8, 32])
+def test_worker_counts(N):
+    """Powers of two take the multiply-by-1/N path, others the division; 32 is the maximum."""
+    rep, st = _custom([4100, 60], N, 2, seed=30 + N)
+    assert rep.ok() and st == 0
+
+
+@pytest.mark.parametrize("fused", [True, False])
+def test_stochastic_rounding(fused):
+    """Unbiased rounding: the GPU draws exactly the oracle's Philox numbers."""
+    rep, st = _custom(RAGGED, 3, 3, cfgkw=dict(rounding=1, seed=0xDEADBEEFCAFE), fused=fused, seed=40)
+    _say("stochastic fused=%s: %s" % (fused, rep.line()))
+    assert rep.ok() and st == 0
+
+
+def test_bias_corrected_flavour():
+    rep, st = _custom([6000, 100], 2, 6, cfgkw=dict(adam_flavor=1, eps=1e-6), seed=50)
+    assert rep.ok() and st == 0
+
+
+def test_extreme_magnitudes_and_subnormals():
+    """Gradients from subnormal to 1e30 in one vector; zero layers; exact zeros."""
+    def sel(t, grads):
+        out = []
+        for g in grads:
+            g = g.copy()
+            n = g.size
+            g[: n // 4] *= np.float32(1e-38)          # subnormal range after scaling
+            g[n // 4: n // 2] *= np.float32(1e30)
+            g[n // 2: n // 2 + 100] = 0.0
+            out.append(g)
+        return out
+    sizes = [2048, 2048, 2048, 2048, 100]
+    rep, st = _custom(sizes, 2, 3, gsel=sel, seed=60)
+    assert rep.ok() and st == 0
+
+    def zero_layer(t, grads):
+        for g in grads:
+            g[4096:4096 + 2048] = 0.0
+        return grads
+    rep, st = _custom([4096, 2048, 512], 2, 2, gsel=zero_layer, seed=61)
+    assert rep.ok() and st == 0
+
+
+def test_nonfinite_gradient_sets_status():
+    gcfg, ocfg = configs()
+    seg_off = [0, 1000, 3000]
+    q = QAdam(gcfg, seg_off, 1)
+    x0 = torch.zeros(3000)
+    ds = DeviceState(q, x0)
+    g = torch.randn(3000) * 0.01
+    g[1500] = float("nan")
+    ds.grads[0].copy_(g)
+    ds.step_fused(1, 1e-3, 0.999)
+    assert q.get_status(clear=True) == 1
+    assert q.get_status() == 0
+    sc = ds.scales[0].cpu().numpy()
+    assert np.isfinite(sc[0]) and np.isnan(sc[1])
+    # codes stay in range, the finite layer is unaffected
+    hs = HostState(3000, 1, x0.numpy())
+    out = oracle_step_layers(ocfg, seg_off, 1, 1e-3, 0.999, [g.numpy()], hs)
+    assert out["status"] == 1
+    gw = ds.host_codes(0)
+    nw0 = 32 * 3
+    assert np.array_equal(gw[:nw0], out["words"][0][:nw0])
+    assert np.array_equal(ds.errs[0][:1000].cpu().numpy(), hs.errs[0][:1000])
+    g[1500] = float("inf")
+    ds.grads[0].copy_(g)
+    ds.step_unfused(2, 1e-3, 0.999)
+    assert q.get_status(clear=True) == 1
+    q.close()
+
+
+def test_empty_vector_and_argument_errors():
+    gcfg, _ = configs()
+    q = QAdam(gcfg, [0], 2)
+    assert q.num_params == 0 and q.grad_code_bytes() == 0
+    e = torch.zeros(0, device="cuda")
+    sc = [torch.zeros(1, device="cuda") for _ in range(2)]
+    cd = [torch.zeros(4, dtype=torch.int32, device="cuda") for _ in range(2)]
+    q.step_fused(1, 1e-3, 0.999, [e, e], [e, e], cd, sc, e, e, e, e, torch.zeros(1, dtype=torch.int8, device="cuda"))
+    torch.cuda.synchronize()
+    q.close()
+    q = QAdam(gcfg, [0, 64], 2)
+    buf = torch.zeros(128, device="cuda")
+    codes = torch.zeros(64, dtype=torch.int32, device="cuda")
+    with pytest.raises(QAdamError) as ei:
+        q.worker_quantize(2, 1, buf[:64], buf[64:], codes, buf[:1])
+    assert ei.value.code == -1
+    with pytest.raises(QAdamError) as ei:
+        q.worker_quantize(0, 1, buf[1:65], buf[64:], codes, buf[:1])       # 4-byte aligned only
+    assert ei.value.code == -2
+    with pytest.raises(QAdamError) as ei:
+        q.worker_quantize(0, 0, buf[:64], buf[64:], codes, buf[:1])        # step is 1-based
+    assert ei.value.code == -1
+    q.close()
+
+
+def test_fused_equals_three_calls_on_device():
+    """qadam_step_fused and the three separate calls give the same bits on the GPU itself."""
+    gcfg, _ = configs(k_g=2, k_x=6)
+    sizes = RAGGED + [20000]
+    seg_off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    P, N = int(seg_off[-1]), 4
+    q = QAdam(gcfg, seg_off, N)
+    g = torch.Generator().manual_seed(5)
+    x0 = torch.randn(P, generator=g) * 0.02
+    a, b = DeviceState(q, x0), DeviceState(q, x0)
+    for t in range(1, 6):
+        for i in range(N):
+            gr = torch.randn(P, generator=g) * 0.01
+            a.grads[i].copy_(gr); b.grads[i].copy_(gr)
+        a.step_fused(t, 1e-3, 0.999)
+        b.step_unfused(t, 1e-3, 0.999)
+        torch.cuda.synchronize()
+        for name in ("x", "m", "v", "werr", "wcodes"):
+            assert torch.equal(getattr(a, name), getattr(b, name)), name
+        for i in range(N):
+            assert torch.equal(a.errs[i], b.errs[i]) and torch.equal(a.codes[i], b.codes[i])
+            assert torch.equal(a.scales[i], b.scales[i])
+    q.close()
+
+
+def test_weight_dequantize_roundtrip():
+    gcfg, ocfg = configs(k_x=6)
+    P = 10000
+    q = QAdam(gcfg, [0, P], 1)
+    x = (torch.rand(P) - 0.5).cuda()
+    werr = torch.zeros(P, device="cuda")
+    wc = torch.zeros(P, dtype=torch.int8, device="cuda")
+    xh = torch.zeros(P, device="cuda")
+    q.weight_quantize(1, x, werr, wc)
+    q.weight_dequantize(wc, xh)
+    torch.cuda.synchronize()
+    want = oracle.qx(ocfg, x.cpu().numpy())[1]
+    assert np.array_equal(xh.cpu().numpy(), want)
+    assert torch.equal(xh + werr, x)
+    q.close()

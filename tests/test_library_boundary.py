@@ -1,0 +1,66 @@
+"""CPU-only checks of the C boundary: the shared library loads, exports every function that
+include/qadam.h declares, and rejects bad arguments before touching the GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "qadam.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(qadam_[a-z_0-9]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2004_14180_amd import binding
+    if not os.path.exists(binding.library_path()):
+        from paper_2004_14180_amd.build import build_library
+        build_library(verbose=False)
+    return binding.load_library()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared_functions()
+    assert len(names) >= 12 and "qadam_step_fused" in names
+    for n in names:
+        assert hasattr(lib, n), n
+    from paper_2004_14180_amd.binding import EXPORTS
+    assert sorted(EXPORTS) == names
+
+
+def test_bad_configs_are_rejected_on_the_host(lib):
+    """Argument validation happens before any HIP call, so it can be exercised without a GPU."""
+    from paper_2004_14180_amd.binding import _Config
+    segs = (C.c_int64 * 3)(0, 10, 20)
+    h = C.c_void_p()
+
+    def init(cfg, segs=segs, L=2, N=2):
+        return lib.qadam_init(C.byref(h), C.byref(cfg), segs, L, N)
+
+    good = dict(struct_size=C.sizeof(_Config), k_g=2, k_x=6, rounding=0, weight_ef=1, adam_flavor=0,
+                beta1=0.9, eps=1e-8, seed=0)
+    for bad in [dict(struct_size=4), dict(k_g=-1), dict(k_g=7), dict(k_x=15), dict(rounding=2),
+                dict(weight_ef=3), dict(beta1=1.0), dict(eps=-1.0)]:
+        cfg = _Config(**{**good, **bad})
+        assert init(cfg) == -1, bad
+        assert lib.qadam_last_error()
+    cfg = _Config(**good)
+    assert init(cfg, N=0) == -1
+    assert init(cfg, N=33) == -3
+    assert init(cfg, segs=(C.c_int64 * 3)(1, 10, 20)) == -1
+    assert init(cfg, segs=(C.c_int64 * 3)(0, 30, 20)) == -1
+    assert lib.qadam_destroy(None) == 0
+    assert lib.qadam_grad_code_bytes(None) == 0
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    from paper_2004_14180_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_LIB_PATH", "/nonexistent/libqadam_hip.so")
+    with pytest.raises(ImportError):
+        binding.load_library()

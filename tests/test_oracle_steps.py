@@ -278,3 +278,36 @@ def test_window_equals_layer(oracle):
         ew = e[a:b].copy()
         code, tie, q = oracle.worker_quantize_window(cfg, g[a:b].copy(), ew, s, j0=128 + a, step=4, worker=1)
         assert np.array_equal(code, full["codes"][a:b]) and np.array_equal(ew, err[a:b])
+
+
+def test_step_window_equals_step(oracle):
+    """With the layer scales given (here: numpy's max of |g+e| in fp32, the definition of the
+    infinity norm), any window of a layer steps to the same bits as inside the whole vector."""
+    n, N = 6000, 3
+    rng = np.random.default_rng(70)
+    segs = [0, 1500, n]
+    for rnd in (0, 1):
+        cfg = OracleConfig(k_g=2, k_x=6, rounding=rnd, seed=3)
+        grads = [(rng.standard_normal(n) * 1e-2).astype(np.float32) for _ in range(N)]
+        e0 = [(rng.standard_normal(n) * 1e-3).astype(np.float32) for _ in range(N)]
+        x0 = (rng.standard_normal(n) * 0.02).astype(np.float32)
+        m0 = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+        v0 = (rng.standard_normal(n) ** 2 * 1e-5).astype(np.float32)
+        w0 = (rng.uniform(-1, 1, n) * 2.0 ** -9).astype(np.float32)
+        x, m, v, w = x0.copy(), m0.copy(), v0.copy(), w0.copy()
+        errs = [e.copy() for e in e0]
+        full = oracle.step_s(cfg, segs, 2, 1e-3, 0.999, grads, errs, x, m, v, w)
+        a, b = 2000, 5003                       # a window inside layer 1
+        scales = [np.max(np.abs(grads[i][1500:] + e0[i][1500:])) for i in range(N)]
+        assert [float(full["scales"][i][1]) for i in range(N)] == [float(s) for s in scales]
+        xw, mw, vw, ww = x0[a:b].copy(), m0[a:b].copy(), v0[a:b].copy(), w0[a:b].copy()
+        ew = [e[a:b].copy() for e in e0]
+        win = oracle.step_s_window(cfg, a, 2, 1e-3, 0.999, scales, [g[a:b].copy() for g in grads], ew,
+                                   xw, mw, vw, ww)
+        for got, want in [(xw, x[a:b]), (mw, m[a:b]), (vw, v[a:b]), (ww, w[a:b]),
+                          (win["wcodes"], full["wcodes"][a:b]), (win["tie_x"], full["tie_x"][a:b])]:
+            assert np.array_equal(got, want)
+        for i in range(N):
+            assert np.array_equal(ew[i], errs[i][a:b])
+            codes = oracle.unpack_all(2, segs, full["words"][i])
+            assert np.array_equal(win["codes"][i], codes[a:b])

@@ -1,0 +1,165 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused Quantized-Adam-with-error-feedback step on one MI355X.
+
+A "step" is one pass of the whole hot path (error-feedback add, per-layer scales, Q_g + residual
+for all N workers, mean, Adam moments, parameter step, Q_x with weight error feedback) through
+qadam_step_fused over one batch of synthetic gradients that is already resident in HBM.
+
+Prints ONE JSON line: parameters updated per second (value), ms per step, the HBM roofline of the
+dominant kernel (the fused main pass, timed with HIP events inside the library on the stream it is
+launched on) and the CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0      # MI355X published HBM3E bandwidth
+
+# HBM bytes per launch of the fused main pass on the default workload, from two rocprofv3 --pmc
+# runs (FETCH_SIZE, WRITE_SIZE) scaled by a copy kernel of known size; see
+# profiles/fused_main_pass_gpt1p3b_pmc.txt.  None until measured for the current kernel.
+MEASURED_TRAFFIC_BYTES = None
+
+
+def algorithmic_bytes_per_param(N, code_bits, wcode_bytes, weight_ef):
+    """Bytes the method itself must move per parameter in the fused main pass, one trip per buffer:
+    per worker read g and e, write e and the packed code; server read and write m, v, x, read and
+    write (or only write) e^x, write the weight code."""
+    worker = 12.0 + code_bits / 8.0
+    server = 24.0 + (8.0 if weight_ef else 4.0) + wcode_bytes
+    return N * worker + server
+
+
+def cpu_baseline(wl, sample_layers, seconds_hint=20.0):
+    """The oracle as it stands, one thread, on a bounded sample of the workload's layers."""
+    import numpy as np
+    import torch
+    from oracle import qadam_oracle as oracle
+    offs = wl.seg_offsets
+    N = wl.num_workers
+    std = wl.layer_std()
+    ocfg = oracle.OracleConfig(k_g=wl.k_g, k_x=wl.k_x, weight_ef=wl.weight_ef, beta1=wl.beta1, eps=wl.eps)
+    g = torch.Generator().manual_seed(1234)
+    total, elapsed = 0, 0.0
+    used = []
+    for l in sample_layers:
+        n = offs[l + 1] - offs[l]
+        s = float(std[l])
+        shared = torch.randn(n, generator=g) * s
+        grads = [(shared + torch.randn(n, generator=g) * (0.5 * s)).numpy() for _ in range(N)]
+        errs = [(torch.randn(n, generator=g) * (0.2 * s)).numpy() for _ in range(N)]
+        x = (torch.randn(n, generator=g) * 0.02).numpy()
+        m = (torch.randn(n, generator=g) * (0.3 * s)).numpy()
+        v = (torch.randn(n, generator=g) * s).square().numpy()
+        w = ((torch.rand(n, generator=g) - 0.5) * 2.0 ** -(wl.k_x + 1)).numpy()
+        t0 = time.perf_counter()
+        oracle.step_s(ocfg, [0, n], 3, wl.lr, wl.beta2, grads, errs, x, m, v, w, index_base=offs[l], want_tie=False)
+        elapsed += time.perf_counter() - t0
+        total += n
+        used.append(l)
+        if elapsed > seconds_hint:
+            break
+    return {"value": total / elapsed, "unit": "params/s", "cores": 1, "kind": "oracle",
+            "sample": "one oracle step (variant S, %d workers) over layers %s of the workload = %d parameters, %.1f s"
+                      % (N, used, total, elapsed)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=5, help="workload 1..5 (default: the 1.3B headline)")
+    ap.add_argument("--shrink", type=int, default=1, help="divide model dims (debugging only)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (logical workers are in-memory shards of one "
+                 "device); --gpus %d is not supported" % args.gpus)
+
+    import torch
+    from paper_2004_14180_amd import QAdam, QAdamConfig
+    from paper_2004_14180_amd.workloads import make_workload
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    wl = make_workload(args.config, shrink=args.shrink)
+    P, N = wl.num_params, wl.num_workers
+    weight_ef = 1
+    cfg = QAdamConfig(k_g=wl.k_g, k_x=wl.k_x, rounding=0, weight_ef=weight_ef, beta1=wl.beta1, eps=wl.eps)
+    q = QAdam(cfg, wl.seg_offsets, N)
+    q.profile_enable(True)
+    code_bits = q.grad_code_bytes() * 8.0 / P
+    wcode_bytes = q.weight_code_bytes() / P
+
+    x = wl.init_weights(dev)
+    z = lambda: torch.zeros(P, dtype=torch.float32, device=dev)
+    m, v, werr = z(), z(), z()
+    errs = [z() for _ in range(N)]
+    grads = [torch.empty(P, dtype=torch.float32, device=dev) for _ in range(N)]
+    codes = [torch.empty(q.grad_code_bytes() // 4, dtype=torch.int32, device=dev) for _ in range(N)]
+    scales = [torch.empty(q.num_segments, dtype=torch.float32, device=dev) for _ in range(N)]
+    wcodes = torch.empty(P, dtype=torch.int8 if wl.k_x <= 6 else torch.int16, device=dev)
+
+    step_ms, scale_ms, main_ms = [], [], []
+    for t in range(1, args.warmup + args.steps + 1):
+        wl.fill_gradients(t, grads)            # untimed: inputs are resident before the clock starts
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        q.step_fused(t, wl.lr, wl.beta2, grads, errs, codes, scales, x, m, v, werr, wcodes)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) * 1e3
+        a, b = q.profile_read()
+        if t > args.warmup:
+            step_ms.append(dt); scale_ms.append(a); main_ms.append(b)
+    status = q.get_status()
+    total_ms = sum(step_ms)
+    ms_per_step = total_ms / len(step_ms)
+    main_avg = sum(main_ms) / len(main_ms)
+    scale_avg = sum(scale_ms) / len(scale_ms)
+
+    a_main = algorithmic_bytes_per_param(N, code_bits, wcode_bytes, weight_ef)
+    achieved = a_main * P / (main_avg * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": "k_fused (main pass of qadam_step_fused)",
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": MEASURED_TRAFFIC_BYTES,
+                "algorithmic_bytes_per_param": a_main,
+                "avg_launch_ms": round(main_avg, 4),
+                "scale_pass": {"algorithmic_bytes_per_param": 8.0 * N, "avg_launch_ms": round(scale_avg, 4),
+                               "achieved": round(8.0 * N * P / (scale_avg * 1e-3) / 1e9, 1)},
+                "whole_step_GBs": round((a_main + 8.0 * N) * P / (ms_per_step * 1e-3) / 1e9, 1)}
+
+    out = {
+        "metric": "parameters updated/sec (full QAdam-EF step)",
+        "value": P / (ms_per_step * 1e-3),
+        "unit": "params/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "config %d: %s, %d logical workers, %d parameters in %d layers, "
+                               "k_g=%d (%d-bit codes), k_x=%d (%d-bit weights), weight_ef=1, nearest rounding"
+                               % (wl.config, wl.name, N, P, len(wl.sizes), wl.k_g, round(code_bits), wl.k_x,
+                                  8 * round(wcode_bytes)),
+                   "worker_elements_per_s": N * P / (ms_per_step * 1e-3),
+                   "status_word": status},
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        # a bounded sample: the first transformer block's attention layers (or the first layers)
+        sizes = wl.sizes
+        pick = [l for l in range(len(sizes)) if 0 < sizes[l] <= 20_000_000][:8] or [0]
+        pick = sorted(pick, key=lambda l: -sizes[l])
+        out["cpu_baseline"] = cpu_baseline(wl, pick)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -157,6 +157,17 @@ int qadam_weight_dequantize(qadam_handle_t h, const void* wcodes_dev, float* xha
 /* Read (and optionally clear) the status word.  Synchronises the given stream. */
 int qadam_get_status(qadam_handle_t h, qadam_status_t* out, int32_t clear, void* stream);
 
+/* Kernel timing for measurements.  When enabled, qadam_step_fused brackets its two passes with HIP
+ * events on the caller's stream; qadam_profile_read waits for the last bracketed call and returns
+ * the durations in milliseconds: scale_pass_ms (the read of g and e that produces the per-layer
+ * scales) and main_pass_ms (the fused worker + server + weight-quantize kernel). */
+typedef struct {
+    float scale_pass_ms;
+    float main_pass_ms;
+} qadam_profile_t;
+int qadam_profile_enable(qadam_handle_t h, int32_t on);
+int qadam_profile_read(qadam_handle_t h, qadam_profile_t* out);
+
 /* Text of the last HIP error seen by this thread's calls (static storage). */
 const char* qadam_last_error(void);
 

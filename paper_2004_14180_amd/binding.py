@@ -22,7 +22,7 @@ EXPORTS = [
     "qadam_init", "qadam_destroy", "qadam_grad_code_bytes", "qadam_weight_code_bytes",
     "qadam_num_params", "qadam_worker_quantize", "qadam_server_step", "qadam_weight_quantize",
     "qadam_step_fused", "qadam_worker_step_w", "qadam_server_apply_w", "qadam_weight_dequantize",
-    "qadam_get_status", "qadam_last_error",
+    "qadam_get_status", "qadam_last_error", "qadam_profile_enable", "qadam_profile_read",
 ]
 
 
@@ -36,6 +36,10 @@ class _Config(C.Structure):
     _fields_ = [("struct_size", C.c_uint32), ("k_g", C.c_int32), ("k_x", C.c_int32),
                 ("rounding", C.c_int32), ("weight_ef", C.c_int32), ("adam_flavor", C.c_int32),
                 ("beta1", C.c_float), ("eps", C.c_float), ("seed", C.c_uint64)]
+
+
+class _Profile(C.Structure):
+    _fields_ = [("scale_pass_ms", C.c_float), ("main_pass_ms", C.c_float)]
 
 
 class _Status(C.Structure):
@@ -90,6 +94,8 @@ def load_library():
     lib.qadam_weight_dequantize.argtypes = [vp, vp, vp, vp]
     lib.qadam_get_status.argtypes = [vp, C.POINTER(_Status), i32, vp]
     lib.qadam_last_error.restype = C.c_char_p
+    lib.qadam_profile_enable.argtypes = [vp, i32]
+    lib.qadam_profile_read.argtypes = [vp, C.POINTER(_Profile)]
     _lib = lib
     return lib
 
@@ -195,6 +201,15 @@ class QAdam:
 
     def weight_dequantize(self, wcodes, xhat, stream=None):
         self._check(self._lib.qadam_weight_dequantize(self._h, _ptr(wcodes), _ptr(xhat), _stream(stream)))
+
+    def profile_enable(self, on=True):
+        self._check(self._lib.qadam_profile_enable(self._h, int(on)))
+
+    def profile_read(self):
+        """(scale_pass_ms, main_pass_ms) of the last qadam_step_fused call; waits for it."""
+        pr = _Profile()
+        self._check(self._lib.qadam_profile_read(self._h, C.byref(pr)))
+        return float(pr.scale_pass_ms), float(pr.main_pass_ms)
 
     def get_status(self, clear=False, stream=None) -> int:
         st = _Status()

@@ -22,6 +22,9 @@ struct qadam_ctx {
     Tile*     d_tiles;
     int32_t   num_tiles;
     uint32_t* d_status;
+    bool       profile;
+    bool       profile_valid;
+    hipEvent_t ev[3];
 };
 
 namespace {
@@ -230,6 +233,8 @@ int qadam_init(qadam_handle_t* out, const qadam_config_t* cfg, const int64_t* se
 int qadam_destroy(qadam_handle_t h)
 {
     if (!h) return QADAM_OK;
+    for (hipEvent_t& e : h->ev)
+        if (e) (void)hipEventDestroy(e);
     if (h->d_tiles) (void)hipFree(h->d_tiles);
     if (h->d_status) (void)hipFree(h->d_status);
     delete h;
@@ -326,8 +331,14 @@ int qadam_step_fused(qadam_handle_t h, int64_t step, float lr, float beta2, cons
     const StepScalars S = make_scalars(h, step, lr, beta2);
     const Launch L = make_launch(h, stream);
     QADAM_HIP(launch_zero_scales(L, W, 0, h->num_workers));
+    if (h->profile) QADAM_HIP(hipEventRecord(h->ev[0], L.stream));
     QADAM_HIP(launch_amax(L, S, W, 0, h->num_workers));
+    if (h->profile) QADAM_HIP(hipEventRecord(h->ev[1], L.stream));
     QADAM_HIP(launch_fused(L, S, W, sp));
+    if (h->profile) {
+        QADAM_HIP(hipEventRecord(h->ev[2], L.stream));
+        h->profile_valid = true;
+    }
     return QADAM_OK;
 }
 
@@ -371,6 +382,29 @@ int qadam_server_apply_w(qadam_handle_t h, int64_t step, const void* const* code
     QADAM_CHECK(check_ptr(x_dev, "x_dev", h->num_params != 0));
     const StepScalars S = make_scalars(h, step, 0.0f, 0.0f);
     QADAM_HIP(launch_server_apply_w(make_launch(h, stream), S, W, x_dev));
+    return QADAM_OK;
+}
+
+int qadam_profile_enable(qadam_handle_t h, int32_t on)
+{
+    QADAM_CHECK(check_handle(h));
+    if (on) {
+        for (hipEvent_t& e : h->ev)
+            if (!e) QADAM_HIP(hipEventCreate(&e));
+    }
+    h->profile = on != 0;
+    h->profile_valid = false;
+    return QADAM_OK;
+}
+
+int qadam_profile_read(qadam_handle_t h, qadam_profile_t* out)
+{
+    QADAM_CHECK(check_handle(h));
+    if (!out) return fail(QADAM_EINVAL, "null profile");
+    if (!h->profile || !h->profile_valid) return fail(QADAM_EINVAL, "no profiled call to read");
+    QADAM_HIP(hipEventSynchronize(h->ev[2]));
+    QADAM_HIP(hipEventElapsedTime(&out->scale_pass_ms, h->ev[0], h->ev[1]));
+    QADAM_HIP(hipEventElapsedTime(&out->main_pass_ms, h->ev[1], h->ev[2]));
     return QADAM_OK;
 }
 

@@ -2,6 +2,7 @@
 // device-resident tile table, and the sequencing of kernel launches for each call.
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -22,6 +23,10 @@ struct qadam_ctx {
     Tile*     d_tiles;
     int32_t   num_tiles;
     uint32_t* d_status;
+    float*    d_inv_scales;     // [num_workers][num_segments]
+    uint32_t* d_tile_max;       // [num_workers][num_tiles]
+    int32_t*  d_seg_tile_begin; // [num_segments + 1]
+    int32_t   xcd_chunked;
     bool       profile;
     bool       profile_valid;
     hipEvent_t ev[3];
@@ -96,13 +101,16 @@ StepScalars make_scalars(const qadam_ctx* h, int64_t step, float lr, float beta2
     }
     S.n_workers_f = (float)h->num_workers;
     S.n_is_pow2 = (h->num_workers & (h->num_workers - 1)) == 0;
+    S.inv_n = 1.0f / (float)h->num_workers;
     return S;
 }
 
 Launch make_launch(const qadam_ctx* h, void* stream)
 {
     Launch L;
-    L.tiles = h->d_tiles; L.num_tiles = h->num_tiles; L.num_segments = h->num_segments;
+    L.tiles = h->d_tiles; L.inv_scales = h->d_inv_scales; L.xcd_chunked = h->xcd_chunked;
+    L.tile_max = h->d_tile_max; L.seg_tile_begin = h->d_seg_tile_begin;
+    L.num_tiles = h->num_tiles; L.num_segments = h->num_segments;
     L.num_params = h->num_params; L.status = h->d_status; L.stream = static_cast<hipStream_t>(stream);
     return L;
 }
@@ -187,11 +195,17 @@ int qadam_init(qadam_handle_t* out, const qadam_config_t* cfg, const int64_t* se
     h->code_bits = 1 + h->mu_bits;
     h->wcode_bytes = cfg->k_x <= 6 ? 1 : 2;
     h->tile_elems = tile_elems_from_env();
+    {
+        const char* x = std::getenv("QADAM_XCD_CHUNKED");      // tuning knob for experiments
+        h->xcd_chunked = x ? (std::atoi(x) != 0) : 0;
+    }
 
     // tile table: segments cut into runs of tile_elems elements
     std::vector<Tile> tiles;
+    std::vector<int32_t> seg_tile_begin(num_segments + 1, 0);
     int64_t word_off = 0;
     for (int l = 0; l < num_segments; ++l) {
+        seg_tile_begin[l] = (int32_t)tiles.size();
         const int64_t a = seg_offsets[l], n = seg_offsets[l + 1] - a;
         const int64_t seg_words = segment_code_words(h->code_bits, n);
         const int64_t used_words = (n + 31) / 32 * h->code_bits;
@@ -210,11 +224,19 @@ int qadam_init(qadam_handle_t* out, const qadam_config_t* cfg, const int64_t* se
     }
     h->code_words = word_off;
     if (tiles.size() > (size_t)0x7fffffff) { delete h; return fail(QADAM_ERANGE, "too many tiles"); }
+    seg_tile_begin[num_segments] = (int32_t)tiles.size();
     h->num_tiles = (int32_t)tiles.size();
 
     hipError_t e = hipGetDevice(&h->device);
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&h->d_status), 256);
     if (e == hipSuccess) e = hipMemset(h->d_status, 0, 256);
+    if (e == hipSuccess && num_segments > 0)
+        e = hipMalloc(reinterpret_cast<void**>(&h->d_inv_scales), sizeof(float) * (size_t)num_segments * num_workers);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&h->d_seg_tile_begin), sizeof(int32_t) * (num_segments + 1));
+    if (e == hipSuccess)
+        e = hipMemcpy(h->d_seg_tile_begin, seg_tile_begin.data(), sizeof(int32_t) * (num_segments + 1), hipMemcpyHostToDevice);
+    if (e == hipSuccess && h->num_tiles > 0)
+        e = hipMalloc(reinterpret_cast<void**>(&h->d_tile_max), sizeof(uint32_t) * (size_t)h->num_tiles * num_workers);
     if (e == hipSuccess && h->num_tiles > 0) {
         e = hipMalloc(reinterpret_cast<void**>(&h->d_tiles), sizeof(Tile) * tiles.size());
         if (e == hipSuccess)
@@ -223,6 +245,9 @@ int qadam_init(qadam_handle_t* out, const qadam_config_t* cfg, const int64_t* se
     if (e != hipSuccess) {
         if (h->d_tiles) (void)hipFree(h->d_tiles);
         if (h->d_status) (void)hipFree(h->d_status);
+        if (h->d_inv_scales) (void)hipFree(h->d_inv_scales);
+        if (h->d_tile_max) (void)hipFree(h->d_tile_max);
+        if (h->d_seg_tile_begin) (void)hipFree(h->d_seg_tile_begin);
         delete h;
         return hip_fail(e, "qadam_init device tables");
     }
@@ -237,6 +262,9 @@ int qadam_destroy(qadam_handle_t h)
         if (e) (void)hipEventDestroy(e);
     if (h->d_tiles) (void)hipFree(h->d_tiles);
     if (h->d_status) (void)hipFree(h->d_status);
+    if (h->d_inv_scales) (void)hipFree(h->d_inv_scales);
+    if (h->d_tile_max) (void)hipFree(h->d_tile_max);
+    if (h->d_seg_tile_begin) (void)hipFree(h->d_seg_tile_begin);
     delete h;
     return QADAM_OK;
 }
@@ -262,8 +290,8 @@ int qadam_worker_quantize(qadam_handle_t h, int32_t worker, int64_t step, const 
     W.codes[worker] = static_cast<uint32_t*>(codes_dev); W.scales[worker] = scales_dev;
     const StepScalars S = make_scalars(h, step, 0.0f, 0.0f);
     const Launch L = make_launch(h, stream);
-    QADAM_HIP(launch_zero_scales(L, W, worker, 1));
     QADAM_HIP(launch_amax(L, S, W, worker, 1));
+    QADAM_HIP(launch_reduce_scales(L, W, worker, 1));
     QADAM_HIP(launch_worker_quantize(L, S, W, worker));
     return QADAM_OK;
 }
@@ -330,9 +358,9 @@ int qadam_step_fused(qadam_handle_t h, int64_t step, float lr, float beta2, cons
     sp.x = x_dev; sp.m = m_dev; sp.v = v_dev; sp.werr = werr_dev; sp.wcodes = wcodes_dev;
     const StepScalars S = make_scalars(h, step, lr, beta2);
     const Launch L = make_launch(h, stream);
-    QADAM_HIP(launch_zero_scales(L, W, 0, h->num_workers));
     if (h->profile) QADAM_HIP(hipEventRecord(h->ev[0], L.stream));
     QADAM_HIP(launch_amax(L, S, W, 0, h->num_workers));
+    QADAM_HIP(launch_reduce_scales(L, W, 0, h->num_workers));
     if (h->profile) QADAM_HIP(hipEventRecord(h->ev[1], L.stream));
     QADAM_HIP(launch_fused(L, S, W, sp));
     if (h->profile) {
@@ -362,9 +390,9 @@ int qadam_worker_step_w(qadam_handle_t h, int32_t worker, int64_t step, float lr
     W.codes[worker] = static_cast<uint32_t*>(codes_dev); W.scales[worker] = scales_dev;
     const StepScalars S = make_scalars(h, step, lr, beta2);
     const Launch L = make_launch(h, stream);
-    QADAM_HIP(launch_zero_scales(L, W, worker, 1));
-    // pass 1: local moments, p = alpha m / sqrt(v + eps) + e parked in the error buffer, scale
+    // pass 1: local moments, p = alpha m / sqrt(v + eps) + e parked in the error buffer, tile maxima
     QADAM_HIP(launch_worker_moments_w(L, S, W, worker));
+    QADAM_HIP(launch_reduce_scales(L, W, worker, 1));
     // pass 2: quantize the parked p
     W.grad[worker] = nullptr;
     QADAM_HIP(launch_worker_quantize(L, S, W, worker));

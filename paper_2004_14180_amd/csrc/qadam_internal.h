@@ -38,6 +38,7 @@ struct StepScalars {
     float    omb1, omb2;                // 1-beta, 1-theta_t (fp32 subtraction done on the host)
     float    lr1, sbc2;                 // flavour 1: lr / (1-beta^t), sqrt(1-theta^t)
     float    n_workers_f;               // (float)N
+    float    inv_n;                     // 1/N, used when N is a power of two (then exact)
     int32_t  n_is_pow2;
 };
 
@@ -61,6 +62,10 @@ struct ServerPtrs {
 
 struct Launch {
     const Tile* tiles;      // device
+    float*      inv_scales; // device, [num_workers][num_segments]: 1/s where the fast quotient is safe, else 0
+    uint32_t*   tile_max;   // device, [num_workers][num_tiles]: per-tile max |p| as a bit pattern
+    const int32_t* seg_tile_begin;  // device, [num_segments + 1]: first tile of every segment
+    int32_t     xcd_chunked;// map workgroups so that each XCD walks one contiguous eighth of the tiles
     int32_t     num_tiles;
     int32_t     num_segments;
     int64_t     num_params;
@@ -69,8 +74,10 @@ struct Launch {
 };
 
 // Launchers (defined in qadam_kernels.hip).  `first_worker`/`num` select the workers a launch covers.
-hipError_t launch_zero_scales(const Launch& L, const WorkerPtrs& W, int first_worker, int num);
+// scales in two stages without atomics: per-tile maxima, then one workgroup per (worker, layer)
+// reduces its tiles and also writes the reciprocal used by the fast quotient
 hipError_t launch_amax(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker, int num);
+hipError_t launch_reduce_scales(const Launch& L, const WorkerPtrs& W, int first_worker, int num);
 hipError_t launch_worker_quantize(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int worker);
 hipError_t launch_server_step(const Launch& L, const StepScalars& S, const WorkerPtrs& W, const ServerPtrs& sp);
 hipError_t launch_weight_quantize(const Launch& L, const StepScalars& S, const float* x, float* werr, void* wcodes);

@@ -6,23 +6,34 @@
 // rules are the ones that matter for that regime on CDNA4:
 //   * 64-wide wavefronts, 256-thread workgroups; a lane owns 4 consecutive fp32 values so every
 //     global access is a 128-bit load/store and a wavefront touches 1 KiB of contiguous memory;
+//     all buffers are touched once per pass, so loads and stores carry the non-temporal hint;
 //   * a workgroup owns one tile (<= 4096 elements of one layer), so all per-layer quantities
 //     (scales, code offsets) are wave-uniform and live in scalar registers;
+//   * the loads of a group of workers are issued together before any arithmetic, so a wavefront
+//     keeps 16-20 KiB in flight and few wavefronts per SIMD suffice to cover HBM latency;
 //   * the per-layer scale is a max over |g+e|: lanes reduce with integer max on the bit pattern
 //     (non-negative floats order like integers; NaN/Inf sort above every finite value and so
 //     surface in the scale), wavefront reduction by cross-lane shuffles, LDS across the four
-//     wavefronts, one atomicMax per workgroup;
+//     wavefronts, one plain store of the tile's maximum; a second small kernel reduces the tiles of
+//     each (worker, layer).  No atomics: thousands of workgroups hitting one freshly zeroed word
+//     at the start of every layer cost more than the whole pass;
 //   * codes are stored as bit planes of 32-element groups; a lane's four codes are combined with
 //     the other seven lanes of its group by three DPP OR steps per plane, so packing costs no
 //     LDS traffic and no scatter;
 //   * fp32 arithmetic is kept bit-reproducible: one rounding per operation (built with
-//     -ffp-contract=off), IEEE division and square root, subnormals kept.
+//     -ffp-contract=off), IEEE division and square root, subnormals kept.  The quotient p/s that
+//     selects the grid level is taken as p * (1/s) and redone with the IEEE division only when it
+//     lands within 8 ulp of a decision threshold, which cannot change any decision (the product
+//     is within 2.5 ulp of the correctly rounded quotient).
 #include <hip/hip_runtime.h>
 
 #include "qadam_internal.h"
 
 namespace qadam {
 namespace {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef short s4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ uint32_t f2u(float f) { return __float_as_uint(f); }
 __device__ __forceinline__ float u2f(uint32_t u) { return __uint_as_float(u); }
@@ -70,70 +81,96 @@ __device__ __forceinline__ void uniforms(const StepScalars& S, int64_t gi, uint3
 // ------------------------------------------------------------------------------------------------
 // Q_g on one value (Sec. 5.1).  r = p / s lies in [-1, 1]; the grid is {0} and 2^(mu-1-k_g),
 // mu = 1..k_g+1.  Nearest point: the midpoint below level 2^-j is 0.75 * 2^-j, i.e. mantissa
-// 0x400000 one exponent lower, so adding 0x400000 to the bit pattern of |r| and taking the
-// exponent field rounds |r| to the nearest power of two with midpoints going up.
+// 0x400000 one exponent lower, so adding 0x400000 to the bit pattern of |r| and keeping the
+// exponent field rounds |r| to the nearest power of two with midpoints going up.  Below the first
+// level 2^-k_g the only midpoint is 2^(-k_g-1) (halfway to zero).
 // ------------------------------------------------------------------------------------------------
 struct QgConst {
-    int top;               // k_g + 1
     int ebias;             // 126 - k_g: exponent field of level mu is mu + ebias
-    uint32_t half_l1_bits; // bit pattern of 2^(-k_g-1), the midpoint between 0 and the first level
+    uint32_t half_l1_bits; // bit pattern of 2^(-k_g-1)
     uint32_t l1_bits;      // bit pattern of 2^-k_g
 };
 
 __device__ __forceinline__ QgConst make_qg(int k_g)
 {
     QgConst c;
-    c.top = k_g + 1;
     c.ebias = 126 - k_g;
     c.half_l1_bits = (uint32_t)(126 - k_g) << 23;
     c.l1_bits = (uint32_t)(127 - k_g) << 23;
     return c;
 }
 
-template <int ROUNDING>
-__device__ __forceinline__ int qg_level(float r, const QgConst& c, float U)
+// bit pattern of the grid point nearest to |r| (0 for the zero level); `zero_below` is
+// half_l1_bits, or 0xffffffff to force every level to zero (invalid scale)
+__device__ __forceinline__ uint32_t qg_nearest_bits(uint32_t ab, const QgConst& c, uint32_t zero_below)
 {
-    const uint32_t ab = f2u(r) & 0x7fffffffu;
-    int mu;
-    if constexpr (ROUNDING == 0) {
-        mu = (int)((ab + 0x00400000u) >> 23) - c.ebias;
-        const int low = ab >= c.half_l1_bits ? 1 : 0;
-        mu = mu < 1 ? low : mu;
-    } else {
-        // neighbours lo <= |r| < hi; go up with probability (|r| - lo) / (hi - lo)
-        int below = (int)(ab >> 23) - c.ebias;
-        below = below < 0 ? 0 : below;
-        const uint32_t lo_bits = below > 0 ? (uint32_t)(below + c.ebias) << 23 : 0u;
-        const uint32_t width_bits = below > 0 ? lo_bits : c.l1_bits;        // hi - lo, a power of two
-        const float inv_width = u2f((254u << 23) - width_bits);              // exact reciprocal
-        const float frac = (u2f(ab) - u2f(lo_bits)) * inv_width;
-        mu = below + (U < frac ? 1 : 0);
-    }
-    return mu > c.top ? c.top : mu;
+    uint32_t lvl = (ab + 0x00400000u) & 0x7f800000u;
+    lvl = lvl > c.l1_bits ? lvl : c.l1_bits;
+    lvl = lvl < 0x3f800000u ? lvl : 0x3f800000u;
+    return ab >= zero_below ? lvl : 0u;
 }
 
-// One worker's share of one lane: p = g + e, level, dequantized value, residual.
-// `valid` is false for a zero or non-finite scale (then every code is 0 and e' = p).
+// unbiased choice between the neighbours lo <= |r| < hi: up with probability (|r|-lo)/(hi-lo)
+__device__ __forceinline__ uint32_t qg_stochastic_bits(uint32_t ab, const QgConst& c, float U, bool valid)
+{
+    if (ab >= 0x3f800000u) return valid ? 0x3f800000u : 0u;
+    uint32_t lo = ab & 0x7f800000u;                         // largest power of two <= |r|
+    lo = lo >= c.l1_bits ? lo : 0u;                         // below the first level the lower neighbour is 0
+    const uint32_t width = lo ? lo : c.l1_bits;             // hi - lo, a power of two
+    const float inv_width = u2f((254u << 23) - width);      // exact reciprocal
+    const float frac = (u2f(ab) - u2f(lo)) * inv_width;
+    const uint32_t hi = lo ? lo + (1u << 23) : c.l1_bits;
+    const uint32_t lvl = U < frac ? hi : lo;
+    return valid ? lvl : 0u;
+}
+
+// One worker's share of one lane: p = g + e, level, dequantized value q, residual p - q, and the
+// V codes (4 bits each) of the lane.  s is the layer scale, inv_s its reciprocal or 0 when the
+// fast quotient must not be used (tiny, huge, zero or non-finite scale).
 template <int V, int ROUNDING>
-__device__ __forceinline__ void worker_lane(const float (&g)[V], const float (&e)[V], float s, bool valid,
+__device__ __forceinline__ void worker_lane(const float (&g)[V], const float (&e)[V], float s, float inv_s,
                                             const QgConst& c, int mu_bits, const float (&U)[V],
                                             float (&q)[V], float (&enew)[V], uint32_t& codes)
 {
+    float p[V], r[V];
+#pragma unroll
+    for (int j = 0; j < V; ++j) p[j] = g[j] + e[j];
+    const bool valid = s > 0.0f && s < __builtin_inff();
+    if (ROUNDING == 0 && inv_s != 0.0f) {
+        uint32_t near = 0;
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            r[j] = p[j] * inv_s;
+            // within 8 ulp of a power of two or of 0.75 times one?
+            const uint32_t t = (f2u(r[j]) & 0x7fffffffu) + 0x00400000u;
+            near |= (((t + 8u) & 0x003fffffu) < 16u) ? 1u : 0u;
+        }
+        if (near) {
+#pragma unroll
+            for (int j = 0; j < V; ++j) r[j] = p[j] / s;
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < V; ++j) r[j] = p[j] / s;
+    }
+    const uint32_t zero_below = valid ? c.half_l1_bits : 0xffffffffu;
+    const float s_mul = valid ? s : 0.0f;               // an invalid scale quantizes everything to 0
+    const int sign_shift = 31 - mu_bits;
     codes = 0;
 #pragma unroll
     for (int j = 0; j < V; ++j) {
-        const float p = g[j] + e[j];
-        const float r = p / s;
-        int mu = qg_level<ROUNDING>(r, c, U[j]);
-        mu = valid ? mu : 0;
-        const float lvl = u2f((uint32_t)(mu + c.ebias) << 23);
-        float qa = s * lvl;                       // s * 2^(mu-1-k_g)
-        qa = mu > 0 ? qa : 0.0f;
-        const bool neg = (p < 0.0f) && (mu > 0);
-        const float qv = neg ? -qa : qa;
+        const uint32_t ab = f2u(r[j]) & 0x7fffffffu;
+        uint32_t lvl;
+        if constexpr (ROUNDING == 0) lvl = qg_nearest_bits(ab, c, zero_below);
+        else lvl = qg_stochastic_bits(ab, c, U[j], valid);
+        const float qa = s_mul * u2f(lvl);                // s * 2^(mu-1-k_g); 0 when lvl == 0
+        const uint32_t sign = f2u(p[j]) & 0x80000000u;
+        const float qv = u2f(f2u(qa) | sign);
         q[j] = qv;
-        enew[j] = p - qv;
-        codes |= (uint32_t)(mu | ((neg ? 1 : 0) << mu_bits)) << (4 * j);
+        enew[j] = p[j] - qv;
+        const int mu = max((int)(lvl >> 23) - c.ebias, 0);
+        const uint32_t code = mu > 0 ? ((uint32_t)mu | (sign >> sign_shift)) : 0u;
+        codes |= code << (4 * j);
     }
 }
 
@@ -141,19 +178,20 @@ __device__ __forceinline__ void worker_lane(const float (&g)[V], const float (&e
 __device__ __forceinline__ float qg_decode(uint32_t code, float s, const QgConst& c, int mu_bits)
 {
     const int mu = (int)(code & ((1u << mu_bits) - 1u));
-    const bool neg = (code >> mu_bits) & 1u;
+    const uint32_t sign = ((code >> mu_bits) & 1u) << 31;
     const float lvl = u2f((uint32_t)(mu + c.ebias) << 23);
     float qa = s * lvl;
     qa = mu > 0 ? qa : 0.0f;
-    return neg ? -qa : qa;
+    return u2f(f2u(qa) | sign);
 }
 
 // ------------------------------------------------------------------------------------------------
 // Bit-plane packing.  V == 4: a lane holds the codes of elements 4*lane..4*lane+3 of a 256-element
 // wave chunk as four nibbles of `codes`; the 8 lanes 8G..8G+7 form 32-element group G.  For plane k
-// every lane shifts its 4 plane bits to position 4*(lane%8) and the group ORs them with three DPP
-// steps (swap within pairs, swap pairs within quads, mirror the two quads of a half row).  Lane
-// 8G+k keeps word k.  Must be called with all 64 lanes active.
+// every lane gathers its 4 plane bits (a multiply moves bits 0,4,8,12 to bits 9..12), shifts them
+// to position 4*(lane%8) and the group ORs them with three DPP steps (swap within pairs, swap
+// pairs within quads, mirror the two quads of a half row).  Lane 8G+k keeps word k.  Must be
+// called with all 64 lanes active.
 // V == 1: lane = element; a wave ballot of plane k is the two words of the chunk's two groups.
 // ------------------------------------------------------------------------------------------------
 __device__ __forceinline__ uint32_t dpp_or8(uint32_t w)
@@ -175,8 +213,8 @@ __device__ __forceinline__ uint32_t pack_planes(uint32_t codes, int code_bits, i
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             if (k < code_bits) {
-                const uint32_t t = (codes >> k) & 0x1111u;
-                const uint32_t nib = (t | (t >> 3) | (t >> 6) | (t >> 9)) & 0xFu;
+                const uint32_t t = codes & (0x1111u << k);
+                const uint32_t nib = ((t * 0x249u) >> (9 + k)) & 0xFu;
                 const uint32_t w = dpp_or8(nib << sh);
                 sel = sub == k ? w : sel;
             }
@@ -226,14 +264,15 @@ __device__ __forceinline__ uint32_t unpack_planes(const uint32_t* __restrict__ c
 }
 
 // ------------------------------------------------------------------------------------------------
-// guarded vector access: 128-bit when the lane's V=4 elements are all inside the tile
+// guarded vector access: one 128-bit non-temporal access when the lane's V=4 elements are all
+// inside the tile (every buffer is streamed exactly once per pass)
 // ------------------------------------------------------------------------------------------------
 template <int V>
 __device__ __forceinline__ void load_v(const float* __restrict__ p, int nvalid, float (&out)[V])
 {
     if constexpr (V == 4) {
         if (nvalid == 4) {
-            const float4 t = *reinterpret_cast<const float4*>(p);
+            const f4 t = __builtin_nontemporal_load(reinterpret_cast<const f4*>(p));
             out[0] = t.x; out[1] = t.y; out[2] = t.z; out[3] = t.w;
         } else {
 #pragma unroll
@@ -249,7 +288,9 @@ __device__ __forceinline__ void store_v(float* __restrict__ p, int nvalid, const
 {
     if constexpr (V == 4) {
         if (nvalid == 4) {
-            *reinterpret_cast<float4*>(p) = make_float4(in[0], in[1], in[2], in[3]);
+            f4 t;
+            t.x = in[0]; t.y = in[1]; t.z = in[2]; t.w = in[3];
+            __builtin_nontemporal_store(t, reinterpret_cast<f4*>(p));
         } else {
 #pragma unroll
             for (int j = 0; j < 4; ++j) if (j < nvalid) p[j] = in[j];
@@ -267,7 +308,9 @@ __device__ __forceinline__ void store_wcodes(void* __restrict__ base, int wcode_
         int8_t* p = static_cast<int8_t*>(base) + gi;
         if constexpr (V == 4) {
             if (nvalid == 4) {
-                *reinterpret_cast<char4*>(p) = make_char4((signed char)j[0], (signed char)j[1], (signed char)j[2], (signed char)j[3]);
+                const uint32_t packed = ((uint32_t)j[0] & 0xFFu) | (((uint32_t)j[1] & 0xFFu) << 8) |
+                                        (((uint32_t)j[2] & 0xFFu) << 16) | ((uint32_t)j[3] << 24);
+                __builtin_nontemporal_store(packed, reinterpret_cast<uint32_t*>(p));
                 return;
             }
         }
@@ -277,7 +320,9 @@ __device__ __forceinline__ void store_wcodes(void* __restrict__ base, int wcode_
         int16_t* p = static_cast<int16_t*>(base) + gi;
         if constexpr (V == 4) {
             if (nvalid == 4) {
-                *reinterpret_cast<short4*>(p) = make_short4((short)j[0], (short)j[1], (short)j[2], (short)j[3]);
+                s4 t;
+                t.x = (short)j[0]; t.y = (short)j[1]; t.z = (short)j[2]; t.w = (short)j[3];
+                __builtin_nontemporal_store(t, reinterpret_cast<s4*>(p));
                 return;
             }
         }
@@ -307,8 +352,8 @@ __device__ __forceinline__ float adam_step(const StepScalars& S, float gbar, flo
 
 __device__ __forceinline__ float mean_over_workers(const StepScalars& S, float acc)
 {
-    // N a power of two: multiplying by 1/N rounds exactly like dividing by N
-    return S.n_is_pow2 ? acc * (1.0f / S.n_workers_f) : acc / S.n_workers_f;
+    // N a power of two: multiplying by the exact 1/N rounds exactly like dividing by N
+    return S.n_is_pow2 ? acc * S.inv_n : acc / S.n_workers_f;
 }
 
 // Q_x on one value (Sec. 5.1): nearest multiple of 2^-(k_x+1), saturated to [-1/2, 1/2].
@@ -352,19 +397,40 @@ __device__ __forceinline__ void weight_lane(const StepScalars& S, const float (&
 }
 
 // ------------------------------------------------------------------------------------------------
+// workgroup -> tile.  Workgroups are dealt round-robin to the 8 XCDs; with `xcd_chunked` each XCD
+// walks one contiguous eighth of the tile table instead of every eighth tile.
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ int tile_index(int num_tiles, int xcd_chunked)
+{
+    const int b = blockIdx.x;
+    if (!xcd_chunked) return b;
+    const int per = (num_tiles + 7) >> 3;
+    return (b & 7) * per + (b >> 3);
+}
+
+__host__ int grid_tiles(int num_tiles, int xcd_chunked)
+{
+    return xcd_chunked ? ((num_tiles + 7) / 8) * 8 : num_tiles;
+}
+
+// ------------------------------------------------------------------------------------------------
 // kernel argument blocks
 // ------------------------------------------------------------------------------------------------
 struct AmaxArgs {
     const Tile* tiles;
+    int num_tiles, xcd_chunked;
     const float* grad[QADAM_MAX_WORKERS];
     const float* err[QADAM_MAX_WORKERS];
-    float* scales[QADAM_MAX_WORKERS];
+    uint32_t* tile_max;     // [N][num_tiles]
     int first_worker;
 };
 
 struct FusedArgs {
     const Tile* tiles;
+    int num_tiles, xcd_chunked;
     uint32_t* status;
+    const float* inv_scales;      // [N][L]
+    int num_segments;
     StepScalars S;
     ServerPtrs sp;
     const float* grad[QADAM_MAX_WORKERS];
@@ -375,33 +441,29 @@ struct FusedArgs {
 
 struct WorkerArgs {        // one worker
     const Tile* tiles;
+    int num_tiles, xcd_chunked;
     uint32_t* status;
     StepScalars S;
     const float* grad;     // variant S: g;  variant W second pass: null (p was parked in err)
     float* err;
     uint32_t* codes;
     const float* scales;
+    const float* inv_scales;   // this worker's row
     int worker;
 };
 
-struct ZeroArgs {
+struct ScaleArgs {
     float* scales[QADAM_MAX_WORKERS];
-    int first_worker, num, num_segments;
+    float* inv_scales;
+    const uint32_t* tile_max;
+    const int32_t* seg_tile_begin;
+    int first_worker, num_segments, num_tiles;
 };
 
 // ------------------------------------------------------------------------------------------------
-// scales: zero, then per-(worker, layer) max |g + e|
+// scales: per-tile max |g + e| (k_amax), then per (worker, layer) the max over the layer's tiles
+// and its reciprocal for the fast quotient (k_reduce_scales)
 // ------------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(kBlockThreads) k_zero_scales(ZeroArgs A)
-{
-    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-    const int total = A.num * A.num_segments;
-    if (idx < total) {
-        const int w = idx / A.num_segments, l = idx - w * A.num_segments;
-        A.scales[A.first_worker + w][l] = 0.0f;
-    }
-}
-
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
 {
 #pragma unroll
@@ -412,21 +474,38 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
     return v;
 }
 
-// block-wide max of the lanes' values, then one atomic on the (worker, layer) word
-__device__ __forceinline__ void block_max_to_scale(uint32_t local, float* scale_word)
+// block-wide max of the lanes' values; thread 0 gets the result
+__device__ __forceinline__ uint32_t block_max(uint32_t local)
 {
     __shared__ uint32_t wave_part[kBlockThreads / 64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint32_t wm = wave_max_u32(local);
     if (lane == 0) wave_part[wave] = wm;
     __syncthreads();
-    if (threadIdx.x == 0) {
-        uint32_t bm = wave_part[0];
+    uint32_t bm = wave_part[0];
 #pragma unroll
-        for (int w = 1; w < kBlockThreads / 64; ++w) bm = wave_part[w] > bm ? wave_part[w] : bm;
-        uint32_t* word = reinterpret_cast<uint32_t*>(scale_word);
-        // the word only grows, so a value already >= ours needs no atomic
-        if (bm > __atomic_load_n(word, __ATOMIC_RELAXED)) atomicMax(word, bm);
+    for (int w = 1; w < kBlockThreads / 64; ++w) bm = wave_part[w] > bm ? wave_part[w] : bm;
+    return bm;
+}
+
+// grid: (layers, workers).  One workgroup folds the tile maxima of its (worker, layer).
+__global__ void __launch_bounds__(kBlockThreads) k_reduce_scales(ScaleArgs A)
+{
+    const int l = blockIdx.x, w = A.first_worker + blockIdx.y;
+    const int t0 = A.seg_tile_begin[l], t1 = A.seg_tile_begin[l + 1];
+    const uint32_t* part = A.tile_max + (size_t)w * A.num_tiles;
+    uint32_t local = 0;
+    for (int t = t0 + threadIdx.x; t < t1; t += kBlockThreads) {
+        const uint32_t v = part[t];
+        local = v > local ? v : local;
+    }
+    const uint32_t bm = block_max(local);
+    if (threadIdx.x == 0) {
+        const float s = u2f(bm);
+        A.scales[w][l] = s;
+        // 1/s must be a normal number with full precision for the error bound of the fast quotient
+        const bool ok = s >= 0x1p-100f && s <= 0x1p100f;
+        A.inv_scales[(size_t)w * A.num_segments + l] = ok ? 1.0f / s : 0.0f;
     }
 }
 
@@ -435,6 +514,25 @@ __device__ __forceinline__ uint32_t amax_tile(const float* __restrict__ g, const
 {
     constexpr int BLOCK_ELEMS = kBlockThreads * V;
     uint32_t local = 0;
+    if constexpr (V == 4) {
+        if (t.len == 4 * BLOCK_ELEMS) {
+            // full 4096-element tile: all eight loads of the lane in flight at once
+            float gv[4][4], ev[4][4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                load_v<4>(g + t.start + k * BLOCK_ELEMS + threadIdx.x * 4, 4, gv[k]);
+                load_v<4>(e + t.start + k * BLOCK_ELEMS + threadIdx.x * 4, 4, ev[k]);
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t ab = f2u(gv[k][j] + ev[k][j]) & 0x7fffffffu;
+                    local = ab > local ? ab : local;
+                }
+            return local;
+        }
+    }
     for (int off = threadIdx.x * V; off < t.len; off += BLOCK_ELEMS) {
         const int nvalid = min(t.len - off, V);
         float gv[V], ev[V];
@@ -452,22 +550,23 @@ __device__ __forceinline__ uint32_t amax_tile(const float* __restrict__ g, const
 // grid: (tiles, workers)
 __global__ void __launch_bounds__(kBlockThreads) k_amax(AmaxArgs A)
 {
-    const Tile t = A.tiles[blockIdx.x];
+    const int ti = tile_index(A.num_tiles, A.xcd_chunked);
+    if (ti >= A.num_tiles) return;
+    const Tile t = A.tiles[ti];
     const int w = A.first_worker + blockIdx.y;
     const float* g = A.grad[w];
     const float* e = A.err[w];
     uint32_t local;
     if (t.flags & kTileUnaligned) local = amax_tile<1>(g, e, t);
     else local = amax_tile<4>(g, e, t);
-    block_max_to_scale(local, A.scales[w] + t.seg);
+    const uint32_t bm = block_max(local);
+    if (threadIdx.x == 0) A.tile_max[(size_t)w * A.num_tiles + ti] = bm;
 }
 
 // ------------------------------------------------------------------------------------------------
 // common tile walk: every wave of the block takes 64*V elements per iteration; the trip count is
 // wave-uniform so the cross-lane packing always runs with all lanes active.
 // ------------------------------------------------------------------------------------------------
-__device__ __forceinline__ bool scale_ok(float s) { return s > 0.0f && s < __builtin_inff(); }
-
 __device__ __forceinline__ void write_pad_words(uint32_t* codes, const Tile& t, int code_bits)
 {
     const int pad = (t.flags >> 8) & 3;
@@ -477,18 +576,16 @@ __device__ __forceinline__ void write_pad_words(uint32_t* codes, const Tile& t, 
     }
 }
 
-template <int V>
 __device__ __forceinline__ void store_chunk_words(uint32_t* __restrict__ codes, const Tile& t, int base,
-                                                  int code_bits, int lane, uint32_t word, int word_slot, bool writes)
+                                                  int code_bits, uint32_t word, int word_slot, bool writes)
 {
     // first element of the group this lane's word belongs to
     const int grp = word_slot / code_bits;
     const bool group_live = base + grp * 32 < t.len;
     if (writes && group_live) {
         const int64_t cw = t.code_word + (int64_t)(base >> 5) * code_bits;
-        codes[cw + word_slot] = word;
+        __builtin_nontemporal_store(word, codes + cw + word_slot);
     }
-    (void)lane;
 }
 
 // ---- worker side alone (qadam_worker_quantize, second pass of variant W) -------------------------
@@ -500,7 +597,7 @@ __device__ __forceinline__ void worker_tile(const WorkerArgs& A, const Tile& t)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const QgConst c = make_qg(S.k_g);
     const float s = A.scales[t.seg];
-    const bool valid = scale_ok(s);
+    const float inv_s = A.inv_scales[t.seg];
     if (!(s >= 0.0f && s < __builtin_inff()) && threadIdx.x == 0) atomicOr(A.status, QADAM_STATUS_NONFINITE_SCALE);
     for (int base = wave * WAVE_ELEMS; base < t.len; base += BLOCK_ELEMS) {
         const int off = base + lane * V;
@@ -510,7 +607,7 @@ __device__ __forceinline__ void worker_tile(const WorkerArgs& A, const Tile& t)
 #pragma unroll
         for (int j = 0; j < V; ++j) U[j] = 0.0f;
         if constexpr (PARKED) {
-            // the first pass left p = u + e in the error buffer
+            // the first pass left p = u + e in the error buffer; p + 0 reproduces it
             load_v<V>(A.err + gi, nvalid, g);
 #pragma unroll
             for (int j = 0; j < V; ++j) e[j] = 0.0f;
@@ -520,17 +617,11 @@ __device__ __forceinline__ void worker_tile(const WorkerArgs& A, const Tile& t)
         }
         if constexpr (ROUNDING == 1) uniforms<V>(S, gi, (uint32_t)A.worker, 0u, U);
         uint32_t codes;
-        if constexpr (PARKED) {
-            // p is already rounded; adding +0 keeps it (and keeps -0 apart from the sign of zero,
-            // which no output depends on)
-            worker_lane<V, ROUNDING>(g, e, s, valid, c, S.mu_bits, U, q, en, codes);
-        } else {
-            worker_lane<V, ROUNDING>(g, e, s, valid, c, S.mu_bits, U, q, en, codes);
-        }
+        worker_lane<V, ROUNDING>(g, e, s, inv_s, c, S.mu_bits, U, q, en, codes);
         store_v<V>(A.err + gi, nvalid, en);
         int slot; bool writes;
         const uint32_t word = pack_planes<V>(codes, S.code_bits, lane, slot, writes);
-        store_chunk_words<V>(A.codes, t, base, S.code_bits, lane, word, slot, writes);
+        store_chunk_words(A.codes, t, base, S.code_bits, word, slot, writes);
     }
     write_pad_words(A.codes, t, S.code_bits);
 }
@@ -538,7 +629,9 @@ __device__ __forceinline__ void worker_tile(const WorkerArgs& A, const Tile& t)
 template <int ROUNDING, bool PARKED>
 __global__ void __launch_bounds__(kBlockThreads) k_worker_quantize(WorkerArgs A)
 {
-    const Tile t = A.tiles[blockIdx.x];
+    const int ti = tile_index(A.num_tiles, A.xcd_chunked);
+    if (ti >= A.num_tiles) return;
+    const Tile t = A.tiles[ti];
     if (t.flags & kTileUnaligned) worker_tile<1, ROUNDING, PARKED>(A, t);
     else worker_tile<4, ROUNDING, PARKED>(A, t);
 }
@@ -546,6 +639,7 @@ __global__ void __launch_bounds__(kBlockThreads) k_worker_quantize(WorkerArgs A)
 // ---- server side alone (qadam_server_step) -------------------------------------------------------
 struct ServerArgs {
     const Tile* tiles;
+    int num_tiles, xcd_chunked;
     StepScalars S;
     float* x; float* m; float* v;
     const uint32_t* codes[QADAM_MAX_WORKERS];
@@ -598,7 +692,9 @@ __device__ __forceinline__ void server_tile(const ServerArgs& A, const Tile& t)
 
 __global__ void __launch_bounds__(kBlockThreads) k_server_step(ServerArgs A)
 {
-    const Tile t = A.tiles[blockIdx.x];
+    const int ti = tile_index(A.num_tiles, A.xcd_chunked);
+    if (ti >= A.num_tiles) return;
+    const Tile t = A.tiles[ti];
     if (t.flags & kTileUnaligned) server_tile<1>(A, t);
     else server_tile<4>(A, t);
 }
@@ -650,7 +746,8 @@ __global__ void __launch_bounds__(kBlockThreads) k_weight_dequantize(DequantArgs
 }
 
 // ---- the whole step in one pass (qadam_step_fused) -----------------------------------------------
-template <int V, int ROUNDING>
+// U = number of workers whose loads are issued together (N must be a multiple of U).
+template <int V, int ROUNDING, int U>
 __device__ __forceinline__ void fused_tile(const FusedArgs& A, const Tile& t)
 {
     constexpr int WAVE_ELEMS = 64 * V, BLOCK_ELEMS = (kBlockThreads / 64) * WAVE_ELEMS;
@@ -662,28 +759,7 @@ __device__ __forceinline__ void fused_tile(const FusedArgs& A, const Tile& t)
         const int off = base + lane * V;
         const int nvalid = min(max(t.len - off, 0), V);
         const int64_t gi = t.start + off;
-        float acc[V];
-#pragma unroll
-        for (int j = 0; j < V; ++j) acc[j] = 0.0f;
-        for (int i = 0; i < N; ++i) {
-            const float s = A.scales[i][t.seg];
-            const bool valid = scale_ok(s);
-            float g[V], e[V], q[V], en[V], U[V];
-#pragma unroll
-            for (int j = 0; j < V; ++j) U[j] = 0.0f;
-            load_v<V>(A.grad[i] + gi, nvalid, g);
-            load_v<V>(A.err[i] + gi, nvalid, e);
-            if constexpr (ROUNDING == 1) uniforms<V>(S, gi, (uint32_t)i, 0u, U);
-            uint32_t codes;
-            worker_lane<V, ROUNDING>(g, e, s, valid, c, S.mu_bits, U, q, en, codes);
-            store_v<V>(A.err[i] + gi, nvalid, en);
-            int slot; bool writes;
-            const uint32_t word = pack_planes<V>(codes, S.code_bits, lane, slot, writes);
-            store_chunk_words<V>(A.codes[i], t, base, S.code_bits, lane, word, slot, writes);
-#pragma unroll
-            for (int j = 0; j < V; ++j) acc[j] = acc[j] + q[j];
-        }
-        // server: mean, moments, step, weight quantizer
+        // server state first: its latency hides behind the workers' arithmetic
         float xv[V], mv[V], vv[V], wi[V], wo[V];
         int jc[V];
 #pragma unroll
@@ -692,6 +768,36 @@ __device__ __forceinline__ void fused_tile(const FusedArgs& A, const Tile& t)
         load_v<V>(A.sp.m + gi, nvalid, mv);
         load_v<V>(A.sp.v + gi, nvalid, vv);
         if (S.weight_ef) load_v<V>(A.sp.werr + gi, nvalid, wi);
+        float acc[V];
+#pragma unroll
+        for (int j = 0; j < V; ++j) acc[j] = 0.0f;
+        for (int i0 = 0; i0 < N; i0 += U) {
+            float g[U][V], e[U][V];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                load_v<V>(A.grad[i0 + u] + gi, nvalid, g[u]);
+                load_v<V>(A.err[i0 + u] + gi, nvalid, e[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int i = i0 + u;
+                const float s = A.scales[i][t.seg];
+                const float inv_s = A.inv_scales[(size_t)i * A.num_segments + t.seg];
+                float q[V], en[V], Ur[V];
+#pragma unroll
+                for (int j = 0; j < V; ++j) Ur[j] = 0.0f;
+                if constexpr (ROUNDING == 1) uniforms<V>(S, gi, (uint32_t)i, 0u, Ur);
+                uint32_t codes;
+                worker_lane<V, ROUNDING>(g[u], e[u], s, inv_s, c, S.mu_bits, Ur, q, en, codes);
+                store_v<V>(A.err[i] + gi, nvalid, en);
+                int slot; bool writes;
+                const uint32_t word = pack_planes<V>(codes, S.code_bits, lane, slot, writes);
+                store_chunk_words(A.codes[i], t, base, S.code_bits, word, slot, writes);
+#pragma unroll
+                for (int j = 0; j < V; ++j) acc[j] = acc[j] + q[j];
+            }
+        }
+        // server: mean, moments, step, weight quantizer
 #pragma unroll
         for (int j = 0; j < V; ++j) {
             const float u = adam_step(S, mean_over_workers(S, acc[j]), mv[j], vv[j]);
@@ -712,21 +818,24 @@ __device__ __forceinline__ void fused_tile(const FusedArgs& A, const Tile& t)
     }
 }
 
-template <int ROUNDING>
+template <int ROUNDING, int U>
 __global__ void __launch_bounds__(kBlockThreads) k_fused(FusedArgs A)
 {
-    const Tile t = A.tiles[blockIdx.x];
-    if (t.flags & kTileUnaligned) fused_tile<1, ROUNDING>(A, t);
-    else fused_tile<4, ROUNDING>(A, t);
+    const int ti = tile_index(A.num_tiles, A.xcd_chunked);
+    if (ti >= A.num_tiles) return;
+    const Tile t = A.tiles[ti];
+    if (t.flags & kTileUnaligned) fused_tile<1, ROUNDING, 1>(A, t);
+    else fused_tile<4, ROUNDING, U>(A, t);
 }
 
 // ---- variant W, first pass: local moments, park p = u + e in the error buffer, scale ------------
 struct MomentsWArgs {
     const Tile* tiles;
+    int num_tiles, xcd_chunked;
     StepScalars S;
     const float* grad;
     float* mw; float* vw; float* err;
-    float* scales;
+    uint32_t* tile_max;     // this worker's row
 };
 
 template <int V>
@@ -759,11 +868,14 @@ __device__ __forceinline__ uint32_t moments_w_tile(const MomentsWArgs& A, const 
 
 __global__ void __launch_bounds__(kBlockThreads) k_moments_w(MomentsWArgs A)
 {
-    const Tile t = A.tiles[blockIdx.x];
+    const int ti = tile_index(A.num_tiles, A.xcd_chunked);
+    if (ti >= A.num_tiles) return;
+    const Tile t = A.tiles[ti];
     uint32_t local;
     if (t.flags & kTileUnaligned) local = moments_w_tile<1>(A, t);
     else local = moments_w_tile<4>(A, t);
-    block_max_to_scale(local, A.scales + t.seg);
+    const uint32_t bm = block_max(local);
+    if (threadIdx.x == 0) A.tile_max[ti] = bm;
 }
 
 int grid_for(int64_t work_items, int per_block)
@@ -780,15 +892,14 @@ int grid_for(int64_t work_items, int per_block)
 // ================================================================================================
 // launchers
 // ================================================================================================
-hipError_t launch_zero_scales(const Launch& L, const WorkerPtrs& W, int first_worker, int num)
+hipError_t launch_reduce_scales(const Launch& L, const WorkerPtrs& W, int first_worker, int num)
 {
-    const int total = num * L.num_segments;
-    if (total == 0) return hipSuccess;
-    ZeroArgs A;
+    if (L.num_segments == 0 || num == 0) return hipSuccess;
+    ScaleArgs A;
     for (int i = 0; i < QADAM_MAX_WORKERS; ++i) A.scales[i] = W.scales[i];
-    A.first_worker = first_worker; A.num = num; A.num_segments = L.num_segments;
-    hipLaunchKernelGGL(k_zero_scales, dim3((total + kBlockThreads - 1) / kBlockThreads), dim3(kBlockThreads), 0,
-                       L.stream, A);
+    A.inv_scales = L.inv_scales; A.tile_max = L.tile_max; A.seg_tile_begin = L.seg_tile_begin;
+    A.first_worker = first_worker; A.num_segments = L.num_segments; A.num_tiles = L.num_tiles;
+    hipLaunchKernelGGL(k_reduce_scales, dim3(L.num_segments, num), dim3(kBlockThreads), 0, L.stream, A);
     return hipGetLastError();
 }
 
@@ -797,10 +908,11 @@ hipError_t launch_amax(const Launch& L, const StepScalars& S, const WorkerPtrs& 
     (void)S;
     if (L.num_tiles == 0 || num == 0) return hipSuccess;
     AmaxArgs A;
-    A.tiles = L.tiles;
-    for (int i = 0; i < QADAM_MAX_WORKERS; ++i) { A.grad[i] = W.grad[i]; A.err[i] = W.err[i]; A.scales[i] = W.scales[i]; }
+    A.tiles = L.tiles; A.num_tiles = L.num_tiles; A.xcd_chunked = L.xcd_chunked;
+    for (int i = 0; i < QADAM_MAX_WORKERS; ++i) { A.grad[i] = W.grad[i]; A.err[i] = W.err[i]; }
+    A.tile_max = L.tile_max;
     A.first_worker = first_worker;
-    hipLaunchKernelGGL(k_amax, dim3(L.num_tiles, num), dim3(kBlockThreads), 0, L.stream, A);
+    hipLaunchKernelGGL(k_amax, dim3(grid_tiles(L.num_tiles, L.xcd_chunked), num), dim3(kBlockThreads), 0, L.stream, A);
     return hipGetLastError();
 }
 
@@ -808,11 +920,13 @@ hipError_t launch_worker_quantize(const Launch& L, const StepScalars& S, const W
 {
     if (L.num_tiles == 0) return hipSuccess;
     WorkerArgs A;
-    A.tiles = L.tiles; A.status = L.status; A.S = S;
+    A.tiles = L.tiles; A.num_tiles = L.num_tiles; A.xcd_chunked = L.xcd_chunked;
+    A.status = L.status; A.S = S;
     A.grad = W.grad[worker]; A.err = W.err[worker]; A.codes = W.codes[worker]; A.scales = W.scales[worker];
+    A.inv_scales = L.inv_scales + (size_t)worker * L.num_segments;
     A.worker = worker;
     const bool parked = (A.grad == nullptr);
-    const dim3 grid(L.num_tiles), block(kBlockThreads);
+    const dim3 grid(grid_tiles(L.num_tiles, L.xcd_chunked)), block(kBlockThreads);
     if (S.rounding == 0) {
         if (parked) hipLaunchKernelGGL((k_worker_quantize<0, true>), grid, block, 0, L.stream, A);
         else hipLaunchKernelGGL((k_worker_quantize<0, false>), grid, block, 0, L.stream, A);
@@ -825,7 +939,7 @@ hipError_t launch_worker_quantize(const Launch& L, const StepScalars& S, const W
 
 static void fill_server_args(ServerArgs& A, const Launch& L, const StepScalars& S, const WorkerPtrs& W)
 {
-    A.tiles = L.tiles; A.S = S;
+    A.tiles = L.tiles; A.num_tiles = L.num_tiles; A.xcd_chunked = L.xcd_chunked; A.S = S;
     for (int i = 0; i < QADAM_MAX_WORKERS; ++i) { A.codes[i] = W.codes[i]; A.scales[i] = W.scales[i]; }
 }
 
@@ -835,7 +949,7 @@ hipError_t launch_server_step(const Launch& L, const StepScalars& S, const Worke
     ServerArgs A;
     fill_server_args(A, L, S, W);
     A.x = sp.x; A.m = sp.m; A.v = sp.v; A.apply_only = 0;
-    hipLaunchKernelGGL(k_server_step, dim3(L.num_tiles), dim3(kBlockThreads), 0, L.stream, A);
+    hipLaunchKernelGGL(k_server_step, dim3(grid_tiles(L.num_tiles, L.xcd_chunked)), dim3(kBlockThreads), 0, L.stream, A);
     return hipGetLastError();
 }
 
@@ -845,7 +959,7 @@ hipError_t launch_server_apply_w(const Launch& L, const StepScalars& S, const Wo
     ServerArgs A;
     fill_server_args(A, L, S, W);
     A.x = x; A.m = nullptr; A.v = nullptr; A.apply_only = 1;
-    hipLaunchKernelGGL(k_server_step, dim3(L.num_tiles), dim3(kBlockThreads), 0, L.stream, A);
+    hipLaunchKernelGGL(k_server_step, dim3(grid_tiles(L.num_tiles, L.xcd_chunked)), dim3(kBlockThreads), 0, L.stream, A);
     return hipGetLastError();
 }
 
@@ -877,13 +991,22 @@ hipError_t launch_fused(const Launch& L, const StepScalars& S, const WorkerPtrs&
 {
     if (L.num_tiles == 0) return hipSuccess;
     FusedArgs A;
-    A.tiles = L.tiles; A.status = L.status; A.S = S; A.sp = sp;
+    A.tiles = L.tiles; A.num_tiles = L.num_tiles; A.xcd_chunked = L.xcd_chunked;
+    A.status = L.status; A.inv_scales = L.inv_scales; A.num_segments = L.num_segments; A.S = S; A.sp = sp;
     for (int i = 0; i < QADAM_MAX_WORKERS; ++i) {
         A.grad[i] = W.grad[i]; A.err[i] = W.err[i]; A.codes[i] = W.codes[i]; A.scales[i] = W.scales[i];
     }
-    const dim3 grid(L.num_tiles), block(kBlockThreads);
-    if (S.rounding == 0) hipLaunchKernelGGL(k_fused<0>, grid, block, 0, L.stream, A);
-    else hipLaunchKernelGGL(k_fused<1>, grid, block, 0, L.stream, A);
+    const dim3 grid(grid_tiles(L.num_tiles, L.xcd_chunked)), block(kBlockThreads);
+    const int N = S.num_workers;
+    if (S.rounding == 0) {
+        if (N % 8 == 0) hipLaunchKernelGGL((k_fused<0, 8>), grid, block, 0, L.stream, A);
+        else if (N % 4 == 0) hipLaunchKernelGGL((k_fused<0, 4>), grid, block, 0, L.stream, A);
+        else if (N % 2 == 0) hipLaunchKernelGGL((k_fused<0, 2>), grid, block, 0, L.stream, A);
+        else hipLaunchKernelGGL((k_fused<0, 1>), grid, block, 0, L.stream, A);
+    } else {
+        if (N % 4 == 0) hipLaunchKernelGGL((k_fused<1, 4>), grid, block, 0, L.stream, A);
+        else hipLaunchKernelGGL((k_fused<1, 1>), grid, block, 0, L.stream, A);
+    }
     return hipGetLastError();
 }
 
@@ -891,10 +1014,10 @@ hipError_t launch_worker_moments_w(const Launch& L, const StepScalars& S, const 
 {
     if (L.num_tiles == 0) return hipSuccess;
     MomentsWArgs A;
-    A.tiles = L.tiles; A.S = S;
+    A.tiles = L.tiles; A.num_tiles = L.num_tiles; A.xcd_chunked = L.xcd_chunked; A.S = S;
     A.grad = W.grad[worker]; A.mw = W.mw[worker]; A.vw = W.vw[worker]; A.err = W.err[worker];
-    A.scales = W.scales[worker];
-    hipLaunchKernelGGL(k_moments_w, dim3(L.num_tiles), dim3(kBlockThreads), 0, L.stream, A);
+    A.tile_max = L.tile_max + (size_t)worker * L.num_tiles;
+    hipLaunchKernelGGL(k_moments_w, dim3(grid_tiles(L.num_tiles, L.xcd_chunked)), dim3(kBlockThreads), 0, L.stream, A);
     return hipGetLastError();
 }
 

@@ -169,6 +169,42 @@ def test_extreme_magnitudes_and_subnormals():
     assert rep.ok() and st == 0
 
 
+@pytest.mark.parametrize("k_g", [0, 2, 6])
+def test_values_around_decision_thresholds(k_g):
+    """Gradients placed within +-12 ulp of every rounding threshold of Q_g for many scales: the
+    kernel takes the level from p * (1/s) and falls back to the IEEE quotient near a threshold;
+    every decision must still equal the oracle's, which always divides."""
+    rng = np.random.default_rng(70 + k_g)
+    taus = [2.0 ** (-k_g - 1)] + [0.75 * 2.0 ** -j for j in range(0, k_g)] + [2.0 ** -j for j in range(0, k_g + 1)]
+    sizes, chunks = [], []
+    for trial in range(24):
+        s_val = np.float32(10.0 ** rng.uniform(-30, 30)) if trial % 3 else np.float32(2.0 ** rng.integers(-90, 90))
+        vals = [s_val]
+        for tau in taus:
+            centre = np.float32(np.float64(s_val) * tau)
+            v = centre
+            ups, downs = [], []
+            for _ in range(12):
+                v = np.nextafter(v, np.float32(np.inf)); ups.append(v)
+            v = centre
+            for _ in range(12):
+                v = np.nextafter(v, np.float32(0)); downs.append(v)
+            vals += [centre] + ups + downs
+        arr = np.array(vals, np.float32)
+        arr = np.concatenate([arr, -arr[1:]])
+        arr = np.minimum(np.abs(arr), s_val) * np.sign(arr)       # the scale stays s_val
+        rng.shuffle(arr[1:])
+        chunks.append(arr.astype(np.float32))
+        sizes.append(arr.size)
+    gvec = np.concatenate(chunks)
+
+    def sel(t, grads):
+        return [gvec.copy() for _ in grads]
+    rep, st = _custom(sizes, 2, 2, gsel=sel, cfgkw=dict(k_g=k_g), seed=80)
+    _say("thresholds k_g=%d: %s" % (k_g, rep.line()))
+    assert rep.ok() and st == 0 and rep.ties_g > 0
+
+
 def test_nonfinite_gradient_sets_status():
     gcfg, ocfg = configs()
     seg_off = [0, 1000, 3000]

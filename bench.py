@@ -118,6 +118,9 @@ def main():
         a, b = q.profile_read()
         if t > args.warmup:
             step_ms.append(dt); scale_ms.append(a); main_ms.append(b)
+    if os.environ.get("QADAM_BENCH_VERBOSE"):
+        print("per-step main ms:", [round(v_, 2) for v_ in main_ms], file=sys.stderr)
+        print("per-step scale ms:", [round(v_, 2) for v_ in scale_ms], file=sys.stderr)
     status = q.get_status()
     total_ms = sum(step_ms)
     ms_per_step = total_ms / len(step_ms)

@@ -26,7 +26,6 @@ struct qadam_ctx {
     float*    d_inv_scales;     // [num_workers][num_segments]
     uint32_t* d_tile_max;       // [num_workers][num_tiles]
     int32_t*  d_seg_tile_begin; // [num_segments + 1]
-    int32_t   xcd_chunked;
     bool       profile;
     bool       profile_valid;
     hipEvent_t ev[3];
@@ -108,7 +107,7 @@ StepScalars make_scalars(const qadam_ctx* h, int64_t step, float lr, float beta2
 Launch make_launch(const qadam_ctx* h, void* stream)
 {
     Launch L;
-    L.tiles = h->d_tiles; L.inv_scales = h->d_inv_scales; L.xcd_chunked = h->xcd_chunked;
+    L.tiles = h->d_tiles; L.inv_scales = h->d_inv_scales;
     L.tile_max = h->d_tile_max; L.seg_tile_begin = h->d_seg_tile_begin;
     L.num_tiles = h->num_tiles; L.num_segments = h->num_segments;
     L.num_params = h->num_params; L.status = h->d_status; L.stream = static_cast<hipStream_t>(stream);
@@ -195,10 +194,6 @@ int qadam_init(qadam_handle_t* out, const qadam_config_t* cfg, const int64_t* se
     h->code_bits = 1 + h->mu_bits;
     h->wcode_bytes = cfg->k_x <= 6 ? 1 : 2;
     h->tile_elems = tile_elems_from_env();
-    {
-        const char* x = std::getenv("QADAM_XCD_CHUNKED");      // tuning knob for experiments
-        h->xcd_chunked = x ? (std::atoi(x) != 0) : 0;
-    }
 
     // tile table: segments cut into runs of tile_elems elements
     std::vector<Tile> tiles;

@@ -65,7 +65,6 @@ struct Launch {
     float*      inv_scales; // device, [num_workers][num_segments]: 1/s where the fast quotient is safe, else 0
     uint32_t*   tile_max;   // device, [num_workers][num_tiles]: per-tile max |p| as a bit pattern
     const int32_t* seg_tile_begin;  // device, [num_segments + 1]: first tile of every segment
-    int32_t     xcd_chunked;// map workgroups so that each XCD walks one contiguous eighth of the tiles
     int32_t     num_tiles;
     int32_t     num_segments;
     int64_t     num_params;

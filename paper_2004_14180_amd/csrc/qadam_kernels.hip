@@ -397,28 +397,11 @@ __device__ __forceinline__ void weight_lane(const StepScalars& S, const float (&
 }
 
 // ------------------------------------------------------------------------------------------------
-// workgroup -> tile.  Workgroups are dealt round-robin to the 8 XCDs; with `xcd_chunked` each XCD
-// walks one contiguous eighth of the tile table instead of every eighth tile.
-// ------------------------------------------------------------------------------------------------
-__device__ __forceinline__ int tile_index(int num_tiles, int xcd_chunked)
-{
-    const int b = blockIdx.x;
-    if (!xcd_chunked) return b;
-    const int per = (num_tiles + 7) >> 3;
-    return (b & 7) * per + (b >> 3);
-}
-
-__host__ int grid_tiles(int num_tiles, int xcd_chunked)
-{
-    return xcd_chunked ? ((num_tiles + 7) / 8) * 8 : num_tiles;
-}
-
-// ------------------------------------------------------------------------------------------------
 // kernel argument blocks
 // ------------------------------------------------------------------------------------------------
 struct AmaxArgs {
     const Tile* tiles;
-    int num_tiles, xcd_chunked;
+    int num_tiles;
     const float* grad[QADAM_MAX_WORKERS];
     const float* err[QADAM_MAX_WORKERS];
     uint32_t* tile_max;     // [N][num_tiles]
@@ -427,7 +410,7 @@ struct AmaxArgs {
 
 struct FusedArgs {
     const Tile* tiles;
-    int num_tiles, xcd_chunked;
+    int num_tiles;
     uint32_t* status;
     const float* inv_scales;      // [N][L]
     int num_segments;
@@ -441,7 +424,7 @@ struct FusedArgs {
 
 struct WorkerArgs {        // one worker
     const Tile* tiles;
-    int num_tiles, xcd_chunked;
+    int num_tiles;
     uint32_t* status;
     StepScalars S;
     const float* grad;     // variant S: g;  variant W second pass: null (p was parked in err)
@@ -550,8 +533,7 @@ __device__ __forceinline__ uint32_t amax_tile(const float* __restrict__ g, const
 // grid: (tiles, workers)
 __global__ void __launch_bounds__(kBlockThreads) k_amax(AmaxArgs A)
 {
-    const int ti = tile_index(A.num_tiles, A.xcd_chunked);
-    if (ti >= A.num_tiles) return;
+    const int ti = blockIdx.x;
     const Tile t = A.tiles[ti];
     const int w = A.first_worker + blockIdx.y;
     const float* g = A.grad[w];
@@ -629,8 +611,7 @@ __device__ __forceinline__ void worker_tile(const WorkerArgs& A, const Tile& t)
 template <int ROUNDING, bool PARKED>
 __global__ void __launch_bounds__(kBlockThreads) k_worker_quantize(WorkerArgs A)
 {
-    const int ti = tile_index(A.num_tiles, A.xcd_chunked);
-    if (ti >= A.num_tiles) return;
+    const int ti = blockIdx.x;
     const Tile t = A.tiles[ti];
     if (t.flags & kTileUnaligned) worker_tile<1, ROUNDING, PARKED>(A, t);
     else worker_tile<4, ROUNDING, PARKED>(A, t);
@@ -639,7 +620,7 @@ __global__ void __launch_bounds__(kBlockThreads) k_worker_quantize(WorkerArgs A)
 // ---- server side alone (qadam_server_step) -------------------------------------------------------
 struct ServerArgs {
     const Tile* tiles;
-    int num_tiles, xcd_chunked;
+    int num_tiles;
     StepScalars S;
     float* x; float* m; float* v;
     const uint32_t* codes[QADAM_MAX_WORKERS];
@@ -692,8 +673,7 @@ __device__ __forceinline__ void server_tile(const ServerArgs& A, const Tile& t)
 
 __global__ void __launch_bounds__(kBlockThreads) k_server_step(ServerArgs A)
 {
-    const int ti = tile_index(A.num_tiles, A.xcd_chunked);
-    if (ti >= A.num_tiles) return;
+    const int ti = blockIdx.x;
     const Tile t = A.tiles[ti];
     if (t.flags & kTileUnaligned) server_tile<1>(A, t);
     else server_tile<4>(A, t);
@@ -821,8 +801,7 @@ __device__ __forceinline__ void fused_tile(const FusedArgs& A, const Tile& t)
 template <int ROUNDING, int U>
 __global__ void __launch_bounds__(kBlockThreads) k_fused(FusedArgs A)
 {
-    const int ti = tile_index(A.num_tiles, A.xcd_chunked);
-    if (ti >= A.num_tiles) return;
+    const int ti = blockIdx.x;
     const Tile t = A.tiles[ti];
     if (t.flags & kTileUnaligned) fused_tile<1, ROUNDING, 1>(A, t);
     else fused_tile<4, ROUNDING, U>(A, t);
@@ -831,7 +810,7 @@ __global__ void __launch_bounds__(kBlockThreads) k_fused(FusedArgs A)
 // ---- variant W, first pass: local moments, park p = u + e in the error buffer, scale ------------
 struct MomentsWArgs {
     const Tile* tiles;
-    int num_tiles, xcd_chunked;
+    int num_tiles;
     StepScalars S;
     const float* grad;
     float* mw; float* vw; float* err;
@@ -868,8 +847,7 @@ __device__ __forceinline__ uint32_t moments_w_tile(const MomentsWArgs& A, const 
 
 __global__ void __launch_bounds__(kBlockThreads) k_moments_w(MomentsWArgs A)
 {
-    const int ti = tile_index(A.num_tiles, A.xcd_chunked);
-    if (ti >= A.num_tiles) return;
+    const int ti = blockIdx.x;
     const Tile t = A.tiles[ti];
     uint32_t local;
     if (t.flags & kTileUnaligned) local = moments_w_tile<1>(A, t);
@@ -908,11 +886,11 @@ hipError_t launch_amax(const Launch& L, const StepScalars& S, const WorkerPtrs& 
     (void)S;
     if (L.num_tiles == 0 || num == 0) return hipSuccess;
     AmaxArgs A;
-    A.tiles = L.tiles; A.num_tiles = L.num_tiles; A.xcd_chunked = L.xcd_chunked;
+    A.tiles = L.tiles; A.num_tiles = L.num_tiles;
     for (int i = 0; i < QADAM_MAX_WORKERS; ++i) { A.grad[i] = W.grad[i]; A.err[i] = W.err[i]; }
     A.tile_max = L.tile_max;
     A.first_worker = first_worker;
-    hipLaunchKernelGGL(k_amax, dim3(grid_tiles(L.num_tiles, L.xcd_chunked), num), dim3(kBlockThreads), 0, L.stream, A);
+    hipLaunchKernelGGL(k_amax, dim3(L.num_tiles, num), dim3(kBlockThreads), 0, L.stream, A);
     return hipGetLastError();
 }
 
@@ -920,13 +898,13 @@ hipError_t launch_worker_quantize(const Launch& L, const StepScalars& S, const W
 {
     if (L.num_tiles == 0) return hipSuccess;
     WorkerArgs A;
-    A.tiles = L.tiles; A.num_tiles = L.num_tiles; A.xcd_chunked = L.xcd_chunked;
+    A.tiles = L.tiles; A.num_tiles = L.num_tiles;
     A.status = L.status; A.S = S;
     A.grad = W.grad[worker]; A.err = W.err[worker]; A.codes = W.codes[worker]; A.scales = W.scales[worker];
     A.inv_scales = L.inv_scales + (size_t)worker * L.num_segments;
     A.worker = worker;
     const bool parked = (A.grad == nullptr);
-    const dim3 grid(grid_tiles(L.num_tiles, L.xcd_chunked)), block(kBlockThreads);
+    const dim3 grid(L.num_tiles), block(kBlockThreads);
     if (S.rounding == 0) {
         if (parked) hipLaunchKernelGGL((k_worker_quantize<0, true>), grid, block, 0, L.stream, A);
         else hipLaunchKernelGGL((k_worker_quantize<0, false>), grid, block, 0, L.stream, A);
@@ -939,7 +917,7 @@ hipError_t launch_worker_quantize(const Launch& L, const StepScalars& S, const W
 
 static void fill_server_args(ServerArgs& A, const Launch& L, const StepScalars& S, const WorkerPtrs& W)
 {
-    A.tiles = L.tiles; A.num_tiles = L.num_tiles; A.xcd_chunked = L.xcd_chunked; A.S = S;
+    A.tiles = L.tiles; A.num_tiles = L.num_tiles; A.S = S;
     for (int i = 0; i < QADAM_MAX_WORKERS; ++i) { A.codes[i] = W.codes[i]; A.scales[i] = W.scales[i]; }
 }
 
@@ -949,7 +927,7 @@ hipError_t launch_server_step(const Launch& L, const StepScalars& S, const Worke
     ServerArgs A;
     fill_server_args(A, L, S, W);
     A.x = sp.x; A.m = sp.m; A.v = sp.v; A.apply_only = 0;
-    hipLaunchKernelGGL(k_server_step, dim3(grid_tiles(L.num_tiles, L.xcd_chunked)), dim3(kBlockThreads), 0, L.stream, A);
+    hipLaunchKernelGGL(k_server_step, dim3(L.num_tiles), dim3(kBlockThreads), 0, L.stream, A);
     return hipGetLastError();
 }
 
@@ -959,7 +937,7 @@ hipError_t launch_server_apply_w(const Launch& L, const StepScalars& S, const Wo
     ServerArgs A;
     fill_server_args(A, L, S, W);
     A.x = x; A.m = nullptr; A.v = nullptr; A.apply_only = 1;
-    hipLaunchKernelGGL(k_server_step, dim3(grid_tiles(L.num_tiles, L.xcd_chunked)), dim3(kBlockThreads), 0, L.stream, A);
+    hipLaunchKernelGGL(k_server_step, dim3(L.num_tiles), dim3(kBlockThreads), 0, L.stream, A);
     return hipGetLastError();
 }
 
@@ -991,16 +969,17 @@ hipError_t launch_fused(const Launch& L, const StepScalars& S, const WorkerPtrs&
 {
     if (L.num_tiles == 0) return hipSuccess;
     FusedArgs A;
-    A.tiles = L.tiles; A.num_tiles = L.num_tiles; A.xcd_chunked = L.xcd_chunked;
+    A.tiles = L.tiles; A.num_tiles = L.num_tiles;
     A.status = L.status; A.inv_scales = L.inv_scales; A.num_segments = L.num_segments; A.S = S; A.sp = sp;
     for (int i = 0; i < QADAM_MAX_WORKERS; ++i) {
         A.grad[i] = W.grad[i]; A.err[i] = W.err[i]; A.codes[i] = W.codes[i]; A.scales[i] = W.scales[i];
     }
-    const dim3 grid(grid_tiles(L.num_tiles, L.xcd_chunked)), block(kBlockThreads);
+    const dim3 grid(L.num_tiles), block(kBlockThreads);
     const int N = S.num_workers;
+    // loads of up to four workers in flight per lane: more (eight) costs registers and occupancy
+    // without a measurable gain
     if (S.rounding == 0) {
-        if (N % 8 == 0) hipLaunchKernelGGL((k_fused<0, 8>), grid, block, 0, L.stream, A);
-        else if (N % 4 == 0) hipLaunchKernelGGL((k_fused<0, 4>), grid, block, 0, L.stream, A);
+        if (N % 4 == 0) hipLaunchKernelGGL((k_fused<0, 4>), grid, block, 0, L.stream, A);
         else if (N % 2 == 0) hipLaunchKernelGGL((k_fused<0, 2>), grid, block, 0, L.stream, A);
         else hipLaunchKernelGGL((k_fused<0, 1>), grid, block, 0, L.stream, A);
     } else {
@@ -1014,10 +993,10 @@ hipError_t launch_worker_moments_w(const Launch& L, const StepScalars& S, const 
 {
     if (L.num_tiles == 0) return hipSuccess;
     MomentsWArgs A;
-    A.tiles = L.tiles; A.num_tiles = L.num_tiles; A.xcd_chunked = L.xcd_chunked; A.S = S;
+    A.tiles = L.tiles; A.num_tiles = L.num_tiles; A.S = S;
     A.grad = W.grad[worker]; A.mw = W.mw[worker]; A.vw = W.vw[worker]; A.err = W.err[worker];
     A.tile_max = L.tile_max + (size_t)worker * L.num_tiles;
-    hipLaunchKernelGGL(k_moments_w, dim3(grid_tiles(L.num_tiles, L.xcd_chunked)), dim3(kBlockThreads), 0, L.stream, A);
+    hipLaunchKernelGGL(k_moments_w, dim3(L.num_tiles), dim3(kBlockThreads), 0, L.stream, A);
     return hipGetLastError();
 }
 

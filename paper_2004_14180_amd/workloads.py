@@ -113,6 +113,27 @@ class Workload:
         x = torch.empty(self.num_params, dtype=torch.float32, device=device)
         return x.normal_(0.0, 0.02, generator=g)
 
+    def synthetic_state(self, device, num_workers=None):
+        """A plausible mid-training optimizer state, so that a single step exercises every input:
+        error buffers e_i ~ N(0, (0.2 s_l)^2), m ~ N(0, (0.3 s_l)^2), v = (N(0, s_l^2))^2 and a weight
+        residual uniform within half a grid step of Q_x.  Returns dict(errs, m, v, werr)."""
+        N = self.num_workers if num_workers is None else num_workers
+        P = self.num_params
+        mk = lambda: torch.empty(P, dtype=torch.float32, device=device)
+        errs = []
+        for i in range(N):
+            e = mk()
+            self._fill_layered_normal(e, self._gen(device, "state_e", i), 0.2)
+            errs.append(e)
+        m = mk()
+        self._fill_layered_normal(m, self._gen(device, "state_m"), 0.3)
+        v = mk()
+        self._fill_layered_normal(v, self._gen(device, "state_v"), 1.0)
+        v.square_()
+        werr = torch.rand(P, generator=self._gen(device, "state_w"), device=device, dtype=torch.float32)
+        werr.sub_(0.5).mul_(2.0 ** -(self.k_x + 1))
+        return dict(errs=errs, m=m, v=v, werr=werr)
+
     def _fill_layered_normal(self, out: torch.Tensor, gen: torch.Generator, rel: float):
         offs = self.seg_offsets
         std = self.layer_std()

@@ -1,0 +1,246 @@
+"""GPU parity at the full sizes of the large configurations, in the launch configuration the
+benchmark times (qadam_step_fused, default tile size).
+
+The oracle cannot run 1.3 G parameters x 8 workers in seconds, so these tests check what it can
+compute piece by piece: whole layers (layers are independent: the scale is per layer) and windows
+of the largest layers with the layer's scale taken from its definition, numpy's max of |g + e| in
+fp32.  Inputs are synthetic and seeded (including a synthetic mid-training state, so that one step
+exercises every buffer); nothing fed to the oracle comes from the GPU library.
+"""
+import os
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import qadam_oracle as oracle
+from paper_2004_14180_amd import QAdam
+from paper_2004_14180_amd.workloads import make_workload
+
+from parity_util import THREADS, Report, close, configs, seg_word_offsets
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+class FullRun:
+    """Device buffers of a workload plus host snapshots of the pieces that will be checked."""
+
+    def __init__(self, wl):
+        self.wl = wl
+        dev = torch.device("cuda:0")
+        self.gcfg, self.ocfg = configs(k_g=wl.k_g, k_x=wl.k_x, weight_ef=1, beta1=wl.beta1, eps=wl.eps)
+        self.seg = wl.seg_offsets
+        self.q = QAdam(self.gcfg, self.seg, wl.num_workers)
+        P, N = wl.num_params, wl.num_workers
+        st = wl.synthetic_state(dev)
+        self.errs, self.m, self.v, self.werr = st["errs"], st["m"], st["v"], st["werr"]
+        self.x = wl.init_weights(dev)
+        self.grads = [torch.empty(P, dtype=torch.float32, device=dev) for _ in range(N)]
+        self.codes = [torch.zeros(self.q.grad_code_bytes() // 4, dtype=torch.int32, device=dev) for _ in range(N)]
+        self.scales = [torch.zeros(len(self.seg) - 1, dtype=torch.float32, device=dev) for _ in range(N)]
+        self.wcodes = torch.zeros(P, dtype=torch.int8 if wl.k_x <= 6 else torch.int16, device=dev)
+        self.woffs = seg_word_offsets(wl.k_g, self.seg)
+        self.bits = oracle.grad_code_bits(wl.k_g)
+
+    def host(self, t, a, b):
+        return t[a:b].cpu().numpy().copy()
+
+    def snapshot(self, a, b):
+        """Host copies of every input on [a, b) (taken BEFORE the step: e, x, m, v, e^x change in place)."""
+        return dict(a=a, b=b,
+                    grads=[self.host(g, a, b) for g in self.grads], errs=[self.host(e, a, b) for e in self.errs],
+                    x=self.host(self.x, a, b), m=self.host(self.m, a, b), v=self.host(self.v, a, b),
+                    werr=self.host(self.werr, a, b))
+
+    def step(self, t):
+        wl = self.wl
+        self.q.step_fused(t, wl.lr, wl.beta2, self.grads, self.errs, self.codes, self.scales,
+                          self.x, self.m, self.v, self.werr, self.wcodes)
+        torch.cuda.synchronize()
+        assert self.q.get_status() == 0
+
+    def device_codes(self, i, layer, start_in_layer, n):
+        """Per-element codes of worker i for n elements (multiple of 32) of a layer."""
+        assert start_in_layer % 32 == 0
+        w0 = self.woffs[layer] + start_in_layer // 32 * self.bits
+        nw = (n + 31) // 32 * self.bits
+        words = self.codes[i][w0:w0 + nw].cpu().numpy().view(np.uint32)
+        return oracle.unpack_codes(self.bits, words, n)
+
+    def compare(self, rep, snap, layer, codes_want, wcodes_want, tie_g, tie_x, name):
+        a, b = snap["a"], snap["b"]
+        N = self.wl.num_workers
+        skip = np.zeros(b - a, bool)
+        for i in range(N):
+            got = self.device_codes(i, layer, a - self.seg[layer], b - a)
+            diff = got != codes_want[i]
+            rep.code_mismatch += int(diff.sum())
+            bad = diff & (tie_g[i] == 0)
+            rep.code_mismatch_unflagged += int(bad.sum())
+            assert not bad.any(), "%s: worker %d code mismatch on unflagged elements" % (name, i)
+            rep.ties_g += int(tie_g[i].sum())
+            close(rep, name + " err", self.host(self.errs[i], a, b), snap["errs"][i], diff)
+            skip |= diff
+        close(rep, name + " m", self.host(self.m, a, b), snap["m"], skip)
+        close(rep, name + " v", self.host(self.v, a, b), snap["v"], skip)
+        close(rep, name + " x", self.host(self.x, a, b), snap["x"], skip)
+        wgot = self.host(self.wcodes, a, b)
+        wdiff = (wgot != wcodes_want) & ~skip
+        rep.wcode_mismatch += int(wdiff.sum())
+        rep.ties_x += int(tie_x.sum())
+        assert not (wdiff & (tie_x == 0)).any(), name + ": weight code mismatch on unflagged elements"
+        close(rep, name + " werr", self.host(self.werr, a, b), snap["werr"], skip | wdiff)
+        rep.checked += (b - a) * (N + 1)
+
+
+def check_layers(run, rep, layers, t, snaps):
+    """Oracle step on whole layers (in place on the snapshots), compared with the device."""
+    wl = run.wl
+
+    def one(l):
+        s = snaps[l]
+        out = oracle.step_s(run.ocfg, [0, s["b"] - s["a"]], t, wl.lr, wl.beta2, s["grads"], s["errs"],
+                            s["x"], s["m"], s["v"], s["werr"], index_base=s["a"])
+        assert out["status"] == 0
+        return l, out
+
+    with ThreadPoolExecutor(THREADS) as ex:
+        results = list(ex.map(one, sorted(layers, key=lambda l: -wl.sizes[l])))
+    for l, out in results:
+        n = wl.sizes[l]
+        codes = [oracle.unpack_codes(run.bits, out["words"][i], n) for i in range(wl.num_workers)]
+        for i in range(wl.num_workers):
+            got = float(run.scales[i][l].cpu())
+            assert np.float32(got).view(np.uint32) == out["scales"][i][0].view(np.uint32), "scale layer %d" % l
+        run.compare(rep, snaps[l], l, codes, out["wcodes"], out["tie_g"], out["tie_x"], "layer %d" % l)
+
+
+def check_windows(run, rep, layer, windows, t, snaps, layer_scales):
+    """Oracle step on windows of one (large) layer with the layer scales from numpy."""
+    wl = run.wl
+
+    def one(k):
+        s = snaps[k]
+        out = oracle.step_s_window(run.ocfg, s["a"], t, wl.lr, wl.beta2, layer_scales, s["grads"], s["errs"],
+                                   s["x"], s["m"], s["v"], s["werr"])
+        return k, out
+
+    with ThreadPoolExecutor(THREADS) as ex:
+        results = list(ex.map(one, range(len(windows))))
+    for k, out in results:
+        run.compare(rep, snaps[k], layer, out["codes"], out["wcodes"], out["tie_g"], out["tie_x"],
+                    "layer %d window %d" % (layer, k))
+
+
+def numpy_layer_scales(run, layer, chunk=1 << 25):
+    """||g_i + e_i||_inf of one layer for every worker: fp32 add, abs, max (numpy, on host copies)."""
+    a, b = run.seg[layer], run.seg[layer + 1]
+    out = []
+    for i in range(run.wl.num_workers):
+        s = np.float32(0)
+        for c in range(a, b, chunk):
+            d = min(b, c + chunk)
+            p = run.grads[i][c:d].cpu().numpy() + run.errs[i][c:d].cpu().numpy()
+            s = max(s, np.max(np.abs(p)))
+        out.append(np.float32(s))
+    return out
+
+
+def pick_windows(rng, n, count, length):
+    """Windows inside a layer of n elements: 32-aligned starts, first and last included (ragged end)."""
+    length = min(length, n)
+    starts = {0, max(0, (n - length) // 32 * 32)}
+    while len(starts) < count:
+        starts.add(int(rng.integers(0, max(1, (n - length) // 32))) * 32)
+    return [(s, min(n, s + length)) for s in sorted(starts)]
+
+
+# ----------------------------------------------------------------------------------------------
+def test_config3_gpt2_full_size_one_step():
+    """Config 3 at full size (124 439 808 parameters, 148 layers, 8 workers): every layer whole,
+    except the 38.6 M-element embedding, which is checked on windows."""
+    wl = make_workload(3)
+    run = FullRun(wl)
+    wl.fill_gradients(1, run.grads)
+    rng = np.random.default_rng(3)
+    rep = Report()
+    layers = list(range(1, len(wl.sizes)))
+    snaps = {l: run.snapshot(run.seg[l], run.seg[l + 1]) for l in layers}
+    emb_scales = numpy_layer_scales(run, 0)
+    wins = pick_windows(rng, wl.sizes[0], 12, 1 << 18)
+    wsnaps = [run.snapshot(a, b) for a, b in wins]
+    _say("config3 full: inputs ready")
+    run.step(3)
+    for i in range(wl.num_workers):
+        assert np.float32(run.scales[i][0].cpu()).view(np.uint32) == emb_scales[i].view(np.uint32)
+    check_windows(run, rep, 0, wins, 3, wsnaps, emb_scales)
+    _say("config3 full: embedding windows ok " + rep.line())
+    check_layers(run, rep, layers, 3, snaps)
+    _say("config3 full: " + rep.line())
+    assert rep.ok()
+    run.q.close()
+
+
+def test_config4_adversarial_full_size_windows():
+    """Config 4 at full size (2^28 parameters in one segment, 16 workers): the 16 scales against
+    numpy, and windows of the vector including its first and last elements."""
+    wl = make_workload(4)
+    run = FullRun(wl)
+    wl.fill_gradients(1, run.grads)
+    rng = np.random.default_rng(4)
+    rep = Report()
+    scales = numpy_layer_scales(run, 0)
+    wins = pick_windows(rng, wl.sizes[0], 16, 1 << 17)
+    wsnaps = [run.snapshot(a, b) for a, b in wins]
+    _say("config4 full: inputs ready, scales %s" % [float(s) for s in scales[:4]])
+    run.step(2)
+    for i in range(wl.num_workers):
+        assert np.float32(run.scales[i][0].cpu()).view(np.uint32) == scales[i].view(np.uint32), "scale %d" % i
+    check_windows(run, rep, 0, wins, 2, wsnaps, scales)
+    _say("config4 full: " + rep.line())
+    assert rep.ok()
+    run.q.close()
+
+
+def test_config5_gpt13b_full_size_sampled_layers():
+    """Config 5 at full size (1 315 723 264 parameters, 292 layers, 8 workers; the benchmark's
+    workload and launch configuration): two consecutive steps on whole sampled layers (every
+    2048-element vector, the position embedding, one whole transformer block), and windows of the
+    102.9 M-element token embedding on the first of them."""
+    wl = make_workload(5)
+    run = FullRun(wl)
+    rng = np.random.default_rng(5)
+    rep = Report()
+    block = 7
+    first = 2 + 12 * block
+    layers = [l for l in range(len(wl.sizes)) if wl.sizes[l] <= 8192] + [1] + \
+        [l for l in range(first, first + 12) if wl.sizes[l] > 8192]
+    layers = sorted(set(layers))
+    wl.fill_gradients(1, run.grads)
+    snaps = {l: run.snapshot(run.seg[l], run.seg[l + 1]) for l in layers}
+    emb_scales = numpy_layer_scales(run, 0)
+    wins = pick_windows(rng, wl.sizes[0], 10, 1 << 18)
+    wsnaps = [run.snapshot(a, b) for a, b in wins]
+    _say("config5 full: inputs ready (%d layers = %d parameters, %d embedding windows)"
+         % (len(layers), sum(wl.sizes[l] for l in layers), len(wins)))
+    run.step(4)
+    for i in range(wl.num_workers):
+        assert np.float32(run.scales[i][0].cpu()).view(np.uint32) == emb_scales[i].view(np.uint32)
+    check_windows(run, rep, 0, wins, 4, wsnaps, emb_scales)
+    _say("config5 full: embedding windows ok " + rep.line())
+    check_layers(run, rep, layers, 4, snaps)
+    _say("config5 full step 1: " + rep.line())
+    # second step: the oracle continues from its own state on the sampled layers
+    wl.fill_gradients(2, run.grads)
+    for l in layers:
+        snaps[l]["grads"] = [run.host(g, run.seg[l], run.seg[l + 1]) for g in run.grads]
+    run.step(5)
+    check_layers(run, rep, layers, 5, snaps)
+    _say("config5 full step 2: " + rep.line())
+    assert rep.ok()
+    run.q.close()

@@ -299,3 +299,55 @@ def test_weight_dequantize_roundtrip():
     assert np.array_equal(xh.cpu().numpy(), want)
     assert torch.equal(xh + werr, x)
     q.close()
+
+
+# ------------------------------------------------------------- variant W (Algorithms 2-3 as printed)
+@pytest.mark.parametrize("rounding", [0, 1])
+def test_variant_w_worker_moments(rounding):
+    """Workers own m_i, v_i and quantize alpha m / sqrt(v + eps) + e (Algorithm 3); the server
+    subtracts the mean message (Algorithm 2) and emits Q_x."""
+    gcfg, ocfg = configs(k_g=2, k_x=6, rounding=rounding, seed=77, eps=1e-5)
+    sizes = RAGGED + [20000]
+    seg_off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    P, N = int(seg_off[-1]), 3
+    rng = np.random.default_rng(90 + rounding)
+    q = QAdam(gcfg, seg_off, N)
+    x0 = (rng.standard_normal(P) * 0.02).astype(np.float32)
+    ds = DeviceState(q, torch.from_numpy(x0))
+    mw = [torch.zeros(P, device="cuda") for _ in range(N)]
+    vw = [torch.zeros(P, device="cuda") for _ in range(N)]
+    hx = x0.copy()
+    he = [np.zeros(P, np.float32) for _ in range(N)]
+    hm = [np.zeros(P, np.float32) for _ in range(N)]
+    hv = [np.zeros(P, np.float32) for _ in range(N)]
+    hw = np.zeros(P, np.float32)
+    rep = Report()
+    for t in range(1, 6):
+        grads = [(rng.standard_normal(P) * 1e-2).astype(np.float32) for _ in range(N)]
+        for i in range(N):
+            ds.grads[i].copy_(torch.from_numpy(grads[i]))
+            q.worker_step_w(i, t, 1e-3, 0.999, ds.grads[i], mw[i], vw[i], ds.errs[i], ds.codes[i], ds.scales[i])
+        q.server_apply_w(t, ds.codes, ds.scales, ds.x)
+        q.weight_quantize(t, ds.x, ds.werr, ds.wcodes)
+        out = oracle.step_w(ocfg, seg_off, t, 1e-3, 0.999, grads, he, hm, hv, hx, hw)
+        torch.cuda.synchronize()
+        for i in range(N):
+            assert np.array_equal(ds.host_codes(i), out["words"][i]), "codes of worker %d step %d" % (i, t)
+            assert np.array_equal(ds.scales[i][: len(sizes)].cpu().numpy(), out["scales"][i])
+            from parity_util import close
+            close(rep, "err", ds.errs[i].cpu().numpy(), he[i])
+            close(rep, "mw", mw[i].cpu().numpy(), hm[i])
+            close(rep, "vw", vw[i].cpu().numpy(), hv[i])
+        close(rep, "x", ds.x.cpu().numpy(), hx)
+        close(rep, "werr", ds.werr.cpu().numpy(), hw)
+        assert np.array_equal(ds.wcodes[:P].cpu().numpy(), out["wcodes"])
+    assert q.get_status() == 0 and rep.float_not_bit_exact == 0
+    q.close()
+
+
+def test_small_tile_sizes(monkeypatch):
+    """The tile size is a tuning parameter read at qadam_init; results must not depend on it."""
+    for tile in ("256", "1024", "16384"):
+        monkeypatch.setenv("QADAM_TILE_ELEMS", tile)
+        rep, st = _custom([700, 5000, 257, 33000, 9], 4, 2, seed=95)
+        assert rep.ok() and st == 0, tile

@@ -21,10 +21,10 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0      # MI355X published HBM3E bandwidth
 
-# HBM bytes per launch of the fused main pass on the default workload, from two rocprofv3 --pmc
-# runs (FETCH_SIZE, WRITE_SIZE) scaled by a copy kernel of known size; see
-# profiles/fused_main_pass_gpt1p3b_pmc.txt.  None until measured for the current kernel.
-MEASURED_TRAFFIC_BYTES = None
+# HBM bytes per launch of the fused main pass on the default workload (config 5), from two
+# rocprofv3 --pmc runs (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0 after scaling by a 4 GiB copy of known
+# traffic); summary in profiles/fused_step_gpt1p3b_pmc_traffic.txt.  Other workloads: not measured.
+MEASURED_TRAFFIC_BYTES = {5: 174.33e9}
 
 
 def algorithmic_bytes_per_param(N, code_bits, wcode_bytes, weight_ef):
@@ -78,6 +78,9 @@ def main():
     ap.add_argument("--config", type=int, default=5, help="workload 1..5 (default: the 1.3B headline)")
     ap.add_argument("--shrink", type=int, default=1, help="divide model dims (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 4 GiB device copy (a kernel of known traffic, to scale "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (logical workers are in-memory shards of one "
@@ -107,6 +110,13 @@ def main():
     scales = [torch.empty(q.num_segments, dtype=torch.float32, device=dev) for _ in range(N)]
     wcodes = torch.empty(P, dtype=torch.int8 if wl.k_x <= 6 else torch.int16, device=dev)
 
+    if args.copy_calibration:
+        src = torch.ones(1 << 30, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)                      # reads 4 GiB, writes 4 GiB
+        torch.cuda.synchronize()
+        del src, dst
+
     step_ms, scale_ms, main_ms = [], [], []
     for t in range(1, args.warmup + args.steps + 1):
         wl.fill_gradients(t, grads)            # untimed: inputs are resident before the clock starts
@@ -132,7 +142,7 @@ def main():
     roofline = {"bound": "hbm", "kernel": "k_fused (main pass of qadam_step_fused)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES,
+                "traffic": MEASURED_TRAFFIC_BYTES.get(args.config) if args.shrink == 1 else None,
                 "algorithmic_bytes_per_param": a_main,
                 "avg_launch_ms": round(main_avg, 4),
                 "scale_pass": {"algorithmic_bytes_per_param": 8.0 * N, "avg_launch_ms": round(scale_avg, 4),

@@ -101,8 +101,8 @@ def main():
     code_bits = q.grad_code_bytes() * 8.0 / P
     wcode_bytes = q.weight_code_bytes() / P
 
-    x = wl.init_weights(dev)
     z = lambda: torch.zeros(P, dtype=torch.float32, device=dev)
+    x = wl.init_weights(dev)
     m, v, werr = z(), z(), z()
     errs = [z() for _ in range(N)]
     grads = [torch.empty(P, dtype=torch.float32, device=dev) for _ in range(N)]

@@ -166,11 +166,14 @@ def main():
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:
-        # a bounded sample: the first transformer block's attention layers (or the first layers)
+        # a bounded sample: the first layers after the token embedding, up to ~75 M parameters
+        # (about 10 s of single-threaded oracle work); stops early after ~25 s
         sizes = wl.sizes
-        pick = [l for l in range(len(sizes)) if 0 < sizes[l] <= 20_000_000][:8] or [0]
-        pick = sorted(pick, key=lambda l: -sizes[l])
-        out["cpu_baseline"] = cpu_baseline(wl, pick)
+        pick, tot = [], 0
+        for l in range(len(sizes)):
+            if 0 < sizes[l] <= 20_000_000 and tot < 75_000_000:
+                pick.append(l); tot += sizes[l]
+        out["cpu_baseline"] = cpu_baseline(wl, pick or [0], seconds_hint=25.0)
     print(json.dumps(out), flush=True)
 
 

@@ -77,6 +77,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=5, help="workload 1..5 (default: the 1.3B headline)")
     ap.add_argument("--shrink", type=int, default=1, help="divide model dims (debugging only)")
+    ap.add_argument("--variant", choices=["s", "w"], default="s",
+                    help="s: workers quantize g+e, server owns the moments (the headline path); "
+                         "w: Algorithms 2-3 as printed, workers own the moments (qadam_step_fused_w)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 4 GiB device copy (a kernel of known traffic, to scale "
@@ -106,6 +109,9 @@ def main():
     m, v, werr = z(), z(), z()
     errs = [z() for _ in range(N)]
     grads = [torch.empty(P, dtype=torch.float32, device=dev) for _ in range(N)]
+    if args.variant == "w":
+        mw = [z() for _ in range(N)]
+        vw = [z() for _ in range(N)]
     codes = [torch.empty(q.grad_code_bytes() // 4, dtype=torch.int32, device=dev) for _ in range(N)]
     scales = [torch.empty(q.num_segments, dtype=torch.float32, device=dev) for _ in range(N)]
     wcodes = torch.empty(P, dtype=torch.int8 if wl.k_x <= 6 else torch.int16, device=dev)
@@ -122,7 +128,10 @@ def main():
         wl.fill_gradients(t, grads)            # untimed: inputs are resident before the clock starts
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        q.step_fused(t, wl.lr, wl.beta2, grads, errs, codes, scales, x, m, v, werr, wcodes)
+        if args.variant == "s":
+            q.step_fused(t, wl.lr, wl.beta2, grads, errs, codes, scales, x, m, v, werr, wcodes)
+        else:
+            q.step_fused_w(t, wl.lr, wl.beta2, grads, mw, vw, errs, codes, scales, x, werr, wcodes)
         torch.cuda.synchronize()
         dt = (time.perf_counter() - t0) * 1e3
         a, b = q.profile_read()
@@ -137,9 +146,22 @@ def main():
     main_avg = sum(main_ms) / len(main_ms)
     scale_avg = sum(scale_ms) / len(scale_ms)
 
+    if args.variant == "w":
+        # first pass (dominant): per worker read g, m_i, v_i, e_i and write m_i, v_i, p = 28 B;
+        # second pass: per worker read p, write e and the code; server read/write x and e^x, weight code
+        a_first = 28.0 * N
+        a_second = N * (8.0 + code_bits / 8.0) + 8.0 + (8.0 if weight_ef else 4.0) + wcode_bytes
+        achieved = a_first * P / (scale_avg * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": "k_moments_w (first pass of qadam_step_fused_w)",
+                    "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                    "algorithmic_bytes_per_param": a_first, "avg_launch_ms": round(scale_avg, 4),
+                    "second_pass": {"algorithmic_bytes_per_param": a_second, "avg_launch_ms": round(main_avg, 4),
+                                    "achieved": round(a_second * P / (main_avg * 1e-3) / 1e9, 1)},
+                    "whole_step_GBs": round((a_first + a_second) * P / (ms_per_step * 1e-3) / 1e9, 1)}
     a_main = algorithmic_bytes_per_param(N, code_bits, wcode_bytes, weight_ef)
     achieved = a_main * P / (main_avg * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": "k_fused (main pass of qadam_step_fused)",
+    roofline_s = {"bound": "hbm", "kernel": "k_fused (main pass of qadam_step_fused)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": MEASURED_TRAFFIC_BYTES.get(args.config) if args.shrink == 1 else None,
@@ -148,6 +170,8 @@ def main():
                 "scale_pass": {"algorithmic_bytes_per_param": 8.0 * N, "avg_launch_ms": round(scale_avg, 4),
                                "achieved": round(8.0 * N * P / (scale_avg * 1e-3) / 1e9, 1)},
                 "whole_step_GBs": round((a_main + 8.0 * N) * P / (ms_per_step * 1e-3) / 1e9, 1)}
+    if args.variant == "s":
+        roofline = roofline_s
 
     out = {
         "metric": "parameters updated/sec (full QAdam-EF step)",
@@ -158,14 +182,16 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "config %d: %s, %d logical workers, %d parameters in %d layers, "
-                               "k_g=%d (%d-bit codes), k_x=%d (%d-bit weights), weight_ef=1, nearest rounding"
+                               "k_g=%d (%d-bit codes), k_x=%d (%d-bit weights), weight_ef=1, nearest rounding, %s"
                                % (wl.config, wl.name, N, P, len(wl.sizes), wl.k_g, round(code_bits), wl.k_x,
-                                  8 * round(wcode_bytes)),
+                                  8 * round(wcode_bytes),
+                                  "variant S (server moments)" if args.variant == "s" else
+                                  "variant W (worker moments, Algorithms 2-3)"),
                    "worker_elements_per_s": N * P / (ms_per_step * 1e-3),
                    "status_word": status},
         "roofline": roofline,
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.variant == "s":
         # a bounded sample: the first layers after the token embedding, up to ~75 M parameters
         # (about 10 s of single-threaded oracle work); stops early after ~25 s
         sizes = wl.sizes

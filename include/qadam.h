@@ -151,13 +151,21 @@ int qadam_server_apply_w(qadam_handle_t h, int64_t step,
                          const void* const* codes, const float* const* scales,
                          float* x_dev, void* stream);
 
+/* Variant W, the whole step in one call: identical results, bit for bit, to qadam_worker_step_w for
+ * i = 0..N-1, then qadam_server_apply_w, then qadam_weight_quantize.  grads, mw, vw, errs, codes,
+ * scales: HOST arrays of N device pointers. */
+int qadam_step_fused_w(qadam_handle_t h, int64_t step, float lr, float beta2,
+                       const float* const* grads, float* const* mw, float* const* vw,
+                       float* const* errs, void* const* codes, float* const* scales,
+                       float* x_dev, float* werr_dev, void* wcodes_dev, void* stream);
+
 /* Dequantize weight codes to fp32 (what a worker does with the broadcast of Alg. 2 line 2). */
 int qadam_weight_dequantize(qadam_handle_t h, const void* wcodes_dev, float* xhat_dev, void* stream);
 
 /* Read (and optionally clear) the status word.  Synchronises the given stream. */
 int qadam_get_status(qadam_handle_t h, qadam_status_t* out, int32_t clear, void* stream);
 
-/* Kernel timing for measurements.  When enabled, qadam_step_fused brackets its two passes with HIP
+/* Kernel timing for measurements.  When enabled, qadam_step_fused (and qadam_step_fused_w) bracket their two passes with HIP
  * events on the caller's stream; qadam_profile_read waits for the last bracketed call and returns
  * the durations in milliseconds: scale_pass_ms (the read of g and e that produces the per-layer
  * scales) and main_pass_ms (the fused worker + server + weight-quantize kernel). */

@@ -21,7 +21,7 @@ QADAM_STATUS_NONFINITE_SCALE = 1
 EXPORTS = [
     "qadam_init", "qadam_destroy", "qadam_grad_code_bytes", "qadam_weight_code_bytes",
     "qadam_num_params", "qadam_worker_quantize", "qadam_server_step", "qadam_weight_quantize",
-    "qadam_step_fused", "qadam_worker_step_w", "qadam_server_apply_w", "qadam_weight_dequantize",
+    "qadam_step_fused", "qadam_worker_step_w", "qadam_server_apply_w", "qadam_step_fused_w", "qadam_weight_dequantize",
     "qadam_get_status", "qadam_last_error", "qadam_profile_enable", "qadam_profile_read",
 ]
 
@@ -90,6 +90,8 @@ def load_library():
     lib.qadam_step_fused.argtypes = [vp, i64, f32, f32, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp),
                                      C.POINTER(vp), vp, vp, vp, vp, vp, vp]
     lib.qadam_worker_step_w.argtypes = [vp, i32, i64, f32, f32, vp, vp, vp, vp, vp, vp, vp]
+    lib.qadam_step_fused_w.argtypes = [vp, i64, f32, f32, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp),
+                                       C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), vp, vp, vp, vp]
     lib.qadam_server_apply_w.argtypes = [vp, i64, C.POINTER(vp), C.POINTER(vp), vp, vp]
     lib.qadam_weight_dequantize.argtypes = [vp, vp, vp, vp]
     lib.qadam_get_status.argtypes = [vp, C.POINTER(_Status), i32, vp]
@@ -194,6 +196,12 @@ class QAdam:
         self._check(self._lib.qadam_worker_step_w(self._h, worker, step, lr, beta2, _ptr(grad), _ptr(mw),
                                                   _ptr(vw), _ptr(err), _ptr(codes), _ptr(scales),
                                                   _stream(stream)))
+
+    def step_fused_w(self, step, lr, beta2, grads, mw, vw, errs, codes, scales, x, werr, wcodes, stream=None):
+        self._check(self._lib.qadam_step_fused_w(self._h, step, lr, beta2, _ptr_array(grads), _ptr_array(mw),
+                                                 _ptr_array(vw), _ptr_array(errs), _ptr_array(codes),
+                                                 _ptr_array(scales), _ptr(x), _ptr(werr), _ptr(wcodes),
+                                                 _stream(stream)))
 
     def server_apply_w(self, step, codes, scales, x, stream=None):
         self._check(self._lib.qadam_server_apply_w(self._h, step, _ptr_array(codes), _ptr_array(scales),

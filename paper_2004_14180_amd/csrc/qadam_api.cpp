@@ -386,11 +386,47 @@ int qadam_worker_step_w(qadam_handle_t h, int32_t worker, int64_t step, float lr
     const StepScalars S = make_scalars(h, step, lr, beta2);
     const Launch L = make_launch(h, stream);
     // pass 1: local moments, p = alpha m / sqrt(v + eps) + e parked in the error buffer, tile maxima
-    QADAM_HIP(launch_worker_moments_w(L, S, W, worker));
+    QADAM_HIP(launch_worker_moments_w(L, S, W, worker, 1));
     QADAM_HIP(launch_reduce_scales(L, W, worker, 1));
     // pass 2: quantize the parked p
     W.grad[worker] = nullptr;
     QADAM_HIP(launch_worker_quantize(L, S, W, worker));
+    return QADAM_OK;
+}
+
+int qadam_step_fused_w(qadam_handle_t h, int64_t step, float lr, float beta2, const float* const* grads,
+                       float* const* mw, float* const* vw, float* const* errs, void* const* codes,
+                       float* const* scales, float* x_dev, float* werr_dev, void* wcodes_dev, void* stream)
+{
+    QADAM_CHECK(check_handle(h));
+    if (step < 1) return fail(QADAM_EINVAL, "step < 1");
+    if (!mw || !vw) return fail(QADAM_EINVAL, "null pointer array");
+    const bool empty = h->num_params == 0;
+    WorkerPtrs W;
+    QADAM_CHECK(fill_worker_tables(h, W, grads, errs, codes, scales, true));
+    for (int i = 0; i < h->num_workers; ++i) {
+        QADAM_CHECK(check_ptr(mw[i], "mw[i]", !empty));
+        QADAM_CHECK(check_ptr(vw[i], "vw[i]", !empty));
+        W.mw[i] = mw[i]; W.vw[i] = vw[i];
+    }
+    QADAM_CHECK(check_ptr(x_dev, "x_dev", !empty));
+    QADAM_CHECK(check_ptr(werr_dev, "werr_dev", !empty && h->cfg.weight_ef == 1));
+    QADAM_CHECK(check_ptr(wcodes_dev, "wcodes_dev", !empty));
+    ServerPtrs sp;
+    sp.x = x_dev; sp.m = nullptr; sp.v = nullptr; sp.werr = werr_dev; sp.wcodes = wcodes_dev;
+    const StepScalars S = make_scalars(h, step, lr, beta2);
+    const Launch L = make_launch(h, stream);
+    if (h->profile) QADAM_HIP(hipEventRecord(h->ev[0], L.stream));
+    // pass 1 (all workers): local moments, p parked in the error buffers, tile maxima; then scales
+    QADAM_HIP(launch_worker_moments_w(L, S, W, 0, h->num_workers));
+    QADAM_HIP(launch_reduce_scales(L, W, 0, h->num_workers));
+    if (h->profile) QADAM_HIP(hipEventRecord(h->ev[1], L.stream));
+    // pass 2: quantize every worker's parked p, subtract the mean message, Q_x
+    QADAM_HIP(launch_fused_w(L, S, W, sp));
+    if (h->profile) {
+        QADAM_HIP(hipEventRecord(h->ev[2], L.stream));
+        h->profile_valid = true;
+    }
     return QADAM_OK;
 }
 

@@ -83,7 +83,8 @@ hipError_t launch_weight_quantize(const Launch& L, const StepScalars& S, const f
 hipError_t launch_weight_dequantize(const Launch& L, const StepScalars& S, const void* wcodes, float* xhat);
 hipError_t launch_fused(const Launch& L, const StepScalars& S, const WorkerPtrs& W, const ServerPtrs& sp);
 // variant W
-hipError_t launch_worker_moments_w(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int worker);
+hipError_t launch_worker_moments_w(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker, int num);
+hipError_t launch_fused_w(const Launch& L, const StepScalars& S, const WorkerPtrs& W, const ServerPtrs& sp);
 hipError_t launch_server_apply_w(const Launch& L, const StepScalars& S, const WorkerPtrs& W, float* x);
 
 }  // namespace qadam

@@ -727,7 +727,10 @@ __global__ void __launch_bounds__(kBlockThreads) k_weight_dequantize(DequantArgs
 
 // ---- the whole step in one pass (qadam_step_fused) -----------------------------------------------
 // U = number of workers whose loads are issued together (N must be a multiple of U).
-template <int V, int ROUNDING, int U>
+// W = false: variant S (workers' g and e in, server moments).  W = true: second pass of variant W
+// (the first pass left p_i = alpha m_i / sqrt(v_i + eps) + e_i in the error buffers; the server
+// only subtracts the mean message).
+template <int V, int ROUNDING, int U, bool W>
 __device__ __forceinline__ void fused_tile(const FusedArgs& A, const Tile& t)
 {
     constexpr int WAVE_ELEMS = 64 * V, BLOCK_ELEMS = (kBlockThreads / 64) * WAVE_ELEMS;
@@ -745,8 +748,10 @@ __device__ __forceinline__ void fused_tile(const FusedArgs& A, const Tile& t)
 #pragma unroll
         for (int j = 0; j < V; ++j) wi[j] = 0.0f;
         load_v<V>(A.sp.x + gi, nvalid, xv);
-        load_v<V>(A.sp.m + gi, nvalid, mv);
-        load_v<V>(A.sp.v + gi, nvalid, vv);
+        if constexpr (!W) {
+            load_v<V>(A.sp.m + gi, nvalid, mv);
+            load_v<V>(A.sp.v + gi, nvalid, vv);
+        }
         if (S.weight_ef) load_v<V>(A.sp.werr + gi, nvalid, wi);
         float acc[V];
 #pragma unroll
@@ -755,8 +760,14 @@ __device__ __forceinline__ void fused_tile(const FusedArgs& A, const Tile& t)
             float g[U][V], e[U][V];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                load_v<V>(A.grad[i0 + u] + gi, nvalid, g[u]);
-                load_v<V>(A.err[i0 + u] + gi, nvalid, e[u]);
+                if constexpr (W) {
+                    load_v<V>(A.err[i0 + u] + gi, nvalid, g[u]);       // parked p; p + 0 reproduces it
+#pragma unroll
+                    for (int j = 0; j < V; ++j) e[u][j] = 0.0f;
+                } else {
+                    load_v<V>(A.grad[i0 + u] + gi, nvalid, g[u]);
+                    load_v<V>(A.err[i0 + u] + gi, nvalid, e[u]);
+                }
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -777,15 +788,22 @@ __device__ __forceinline__ void fused_tile(const FusedArgs& A, const Tile& t)
                 for (int j = 0; j < V; ++j) acc[j] = acc[j] + q[j];
             }
         }
-        // server: mean, moments, step, weight quantizer
+        // server: mean, (moments, step,) weight quantizer
+        if constexpr (W) {
 #pragma unroll
-        for (int j = 0; j < V; ++j) {
-            const float u = adam_step(S, mean_over_workers(S, acc[j]), mv[j], vv[j]);
-            xv[j] = xv[j] - u;
+            for (int j = 0; j < V; ++j) xv[j] = xv[j] - mean_over_workers(S, acc[j]);
+        } else {
+#pragma unroll
+            for (int j = 0; j < V; ++j) {
+                const float u = adam_step(S, mean_over_workers(S, acc[j]), mv[j], vv[j]);
+                xv[j] = xv[j] - u;
+            }
         }
         weight_lane<V, ROUNDING>(S, xv, wi, gi, wo, jc);
-        store_v<V>(A.sp.m + gi, nvalid, mv);
-        store_v<V>(A.sp.v + gi, nvalid, vv);
+        if constexpr (!W) {
+            store_v<V>(A.sp.m + gi, nvalid, mv);
+            store_v<V>(A.sp.v + gi, nvalid, vv);
+        }
         store_v<V>(A.sp.x + gi, nvalid, xv);
         if (A.sp.werr) store_v<V>(A.sp.werr + gi, nvalid, wo);
         store_wcodes<V>(A.sp.wcodes, S.wcode_bytes, gi, nvalid, jc);
@@ -798,13 +816,13 @@ __device__ __forceinline__ void fused_tile(const FusedArgs& A, const Tile& t)
     }
 }
 
-template <int ROUNDING, int U>
+template <int ROUNDING, int U, bool W>
 __global__ void __launch_bounds__(kBlockThreads) k_fused(FusedArgs A)
 {
     const int ti = blockIdx.x;
     const Tile t = A.tiles[ti];
-    if (t.flags & kTileUnaligned) fused_tile<1, ROUNDING, 1>(A, t);
-    else fused_tile<4, ROUNDING, U>(A, t);
+    if (t.flags & kTileUnaligned) fused_tile<1, ROUNDING, 1, W>(A, t);
+    else fused_tile<4, ROUNDING, U, W>(A, t);
 }
 
 // ---- variant W, first pass: local moments, park p = u + e in the error buffer, scale ------------
@@ -812,25 +830,29 @@ struct MomentsWArgs {
     const Tile* tiles;
     int num_tiles;
     StepScalars S;
-    const float* grad;
-    float* mw; float* vw; float* err;
-    uint32_t* tile_max;     // this worker's row
+    const float* grad[QADAM_MAX_WORKERS];
+    float* mw[QADAM_MAX_WORKERS];
+    float* vw[QADAM_MAX_WORKERS];
+    float* err[QADAM_MAX_WORKERS];
+    uint32_t* tile_max;     // [N][num_tiles]
+    int first_worker;
 };
 
 template <int V>
-__device__ __forceinline__ uint32_t moments_w_tile(const MomentsWArgs& A, const Tile& t)
+__device__ __forceinline__ uint32_t moments_w_tile(const StepScalars& S, const float* __restrict__ grad,
+                                                   float* __restrict__ mw, float* __restrict__ vw,
+                                                   float* __restrict__ err, const Tile& t)
 {
     constexpr int BLOCK_ELEMS = kBlockThreads * V;
-    const StepScalars& S = A.S;
     uint32_t local = 0;
     for (int off = threadIdx.x * V; off < t.len; off += BLOCK_ELEMS) {
         const int nvalid = min(t.len - off, V);
         const int64_t gi = t.start + off;
         float g[V], mv[V], vv[V], e[V], p[V];
-        load_v<V>(A.grad + gi, nvalid, g);
-        load_v<V>(A.mw + gi, nvalid, mv);
-        load_v<V>(A.vw + gi, nvalid, vv);
-        load_v<V>(A.err + gi, nvalid, e);
+        load_v<V>(grad + gi, nvalid, g);
+        load_v<V>(mw + gi, nvalid, mv);
+        load_v<V>(vw + gi, nvalid, vv);
+        load_v<V>(err + gi, nvalid, e);
 #pragma unroll
         for (int j = 0; j < V; ++j) {
             const float u = adam_step(S, g[j], mv[j], vv[j]);
@@ -838,22 +860,24 @@ __device__ __forceinline__ uint32_t moments_w_tile(const MomentsWArgs& A, const 
             const uint32_t ab = j < nvalid ? (f2u(p[j]) & 0x7fffffffu) : 0u;
             local = ab > local ? ab : local;
         }
-        store_v<V>(A.mw + gi, nvalid, mv);
-        store_v<V>(A.vw + gi, nvalid, vv);
-        store_v<V>(A.err + gi, nvalid, p);
+        store_v<V>(mw + gi, nvalid, mv);
+        store_v<V>(vw + gi, nvalid, vv);
+        store_v<V>(err + gi, nvalid, p);
     }
     return local;
 }
 
+// grid: (tiles, workers)
 __global__ void __launch_bounds__(kBlockThreads) k_moments_w(MomentsWArgs A)
 {
     const int ti = blockIdx.x;
     const Tile t = A.tiles[ti];
+    const int w = A.first_worker + blockIdx.y;
     uint32_t local;
-    if (t.flags & kTileUnaligned) local = moments_w_tile<1>(A, t);
-    else local = moments_w_tile<4>(A, t);
+    if (t.flags & kTileUnaligned) local = moments_w_tile<1>(A.S, A.grad[w], A.mw[w], A.vw[w], A.err[w], t);
+    else local = moments_w_tile<4>(A.S, A.grad[w], A.mw[w], A.vw[w], A.err[w], t);
     const uint32_t bm = block_max(local);
-    if (threadIdx.x == 0) A.tile_max[ti] = bm;
+    if (threadIdx.x == 0) A.tile_max[(size_t)w * A.num_tiles + ti] = bm;
 }
 
 int grid_for(int64_t work_items, int per_block)
@@ -965,7 +989,8 @@ hipError_t launch_weight_dequantize(const Launch& L, const StepScalars& S, const
     return hipGetLastError();
 }
 
-hipError_t launch_fused(const Launch& L, const StepScalars& S, const WorkerPtrs& W, const ServerPtrs& sp)
+static hipError_t launch_fused_any(const Launch& L, const StepScalars& S, const WorkerPtrs& W, const ServerPtrs& sp,
+                                   bool variant_w)
 {
     if (L.num_tiles == 0) return hipSuccess;
     FusedArgs A;
@@ -978,25 +1003,42 @@ hipError_t launch_fused(const Launch& L, const StepScalars& S, const WorkerPtrs&
     const int N = S.num_workers;
     // loads of up to four workers in flight per lane: more (eight) costs registers and occupancy
     // without a measurable gain
+#define QADAM_LAUNCH_FUSED(R, WV)                                                                     \
+    do {                                                                                              \
+        if (N % 4 == 0) hipLaunchKernelGGL((k_fused<R, 4, WV>), grid, block, 0, L.stream, A);         \
+        else if (N % 2 == 0 && R == 0) hipLaunchKernelGGL((k_fused<R, 2, WV>), grid, block, 0, L.stream, A); \
+        else hipLaunchKernelGGL((k_fused<R, 1, WV>), grid, block, 0, L.stream, A);                    \
+    } while (0)
     if (S.rounding == 0) {
-        if (N % 4 == 0) hipLaunchKernelGGL((k_fused<0, 4>), grid, block, 0, L.stream, A);
-        else if (N % 2 == 0) hipLaunchKernelGGL((k_fused<0, 2>), grid, block, 0, L.stream, A);
-        else hipLaunchKernelGGL((k_fused<0, 1>), grid, block, 0, L.stream, A);
+        if (variant_w) QADAM_LAUNCH_FUSED(0, true); else QADAM_LAUNCH_FUSED(0, false);
     } else {
-        if (N % 4 == 0) hipLaunchKernelGGL((k_fused<1, 4>), grid, block, 0, L.stream, A);
-        else hipLaunchKernelGGL((k_fused<1, 1>), grid, block, 0, L.stream, A);
+        if (variant_w) QADAM_LAUNCH_FUSED(1, true); else QADAM_LAUNCH_FUSED(1, false);
     }
+#undef QADAM_LAUNCH_FUSED
     return hipGetLastError();
 }
 
-hipError_t launch_worker_moments_w(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int worker)
+hipError_t launch_fused(const Launch& L, const StepScalars& S, const WorkerPtrs& W, const ServerPtrs& sp)
 {
-    if (L.num_tiles == 0) return hipSuccess;
+    return launch_fused_any(L, S, W, sp, false);
+}
+
+hipError_t launch_fused_w(const Launch& L, const StepScalars& S, const WorkerPtrs& W, const ServerPtrs& sp)
+{
+    return launch_fused_any(L, S, W, sp, true);
+}
+
+hipError_t launch_worker_moments_w(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker, int num)
+{
+    if (L.num_tiles == 0 || num == 0) return hipSuccess;
     MomentsWArgs A;
     A.tiles = L.tiles; A.num_tiles = L.num_tiles; A.S = S;
-    A.grad = W.grad[worker]; A.mw = W.mw[worker]; A.vw = W.vw[worker]; A.err = W.err[worker];
-    A.tile_max = L.tile_max + (size_t)worker * L.num_tiles;
-    hipLaunchKernelGGL(k_moments_w, dim3(L.num_tiles), dim3(kBlockThreads), 0, L.stream, A);
+    for (int i = 0; i < QADAM_MAX_WORKERS; ++i) {
+        A.grad[i] = W.grad[i]; A.mw[i] = W.mw[i]; A.vw[i] = W.vw[i]; A.err[i] = W.err[i];
+    }
+    A.tile_max = L.tile_max;
+    A.first_worker = first_worker;
+    hipLaunchKernelGGL(k_moments_w, dim3(L.num_tiles, num), dim3(kBlockThreads), 0, L.stream, A);
     return hipGetLastError();
 }
 

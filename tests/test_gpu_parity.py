@@ -351,3 +351,48 @@ def test_small_tile_sizes(monkeypatch):
         monkeypatch.setenv("QADAM_TILE_ELEMS", tile)
         rep, st = _custom([700, 5000, 257, 33000, 9], 4, 2, seed=95)
         assert rep.ok() and st == 0, tile
+
+
+@pytest.mark.parametrize("N,rounding", [(4, 0), (3, 0), (2, 1)])
+def test_variant_w_fused_step(N, rounding):
+    """qadam_step_fused_w against the oracle's Algorithms 2-3 and against the separate calls."""
+    gcfg, ocfg = configs(k_g=2, k_x=6, rounding=rounding, seed=5, eps=1e-6)
+    sizes = RAGGED + [30000]
+    seg_off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    P = int(seg_off[-1])
+    rng = np.random.default_rng(120 + N)
+    q = QAdam(gcfg, seg_off, N)
+    x0 = (rng.standard_normal(P) * 0.02).astype(np.float32)
+    a, b = DeviceState(q, torch.from_numpy(x0)), DeviceState(q, torch.from_numpy(x0))
+    zeros = lambda: [torch.zeros(P, device="cuda") for _ in range(N)]
+    amw, avw, bmw, bvw = zeros(), zeros(), zeros(), zeros()
+    hx = x0.copy()
+    he, hm, hv = ([np.zeros(P, np.float32) for _ in range(N)] for _ in range(3))
+    hw = np.zeros(P, np.float32)
+    rep = Report()
+    from parity_util import close
+    for t in range(1, 5):
+        grads = [(rng.standard_normal(P) * 1e-2).astype(np.float32) for _ in range(N)]
+        for i in range(N):
+            a.grads[i].copy_(torch.from_numpy(grads[i])); b.grads[i].copy_(a.grads[i])
+        q.step_fused_w(t, 1e-3, 0.999, a.grads, amw, avw, a.errs, a.codes, a.scales, a.x, a.werr, a.wcodes)
+        for i in range(N):
+            q.worker_step_w(i, t, 1e-3, 0.999, b.grads[i], bmw[i], bvw[i], b.errs[i], b.codes[i], b.scales[i])
+        q.server_apply_w(t, b.codes, b.scales, b.x)
+        q.weight_quantize(t, b.x, b.werr, b.wcodes)
+        out = oracle.step_w(ocfg, seg_off, t, 1e-3, 0.999, grads, he, hm, hv, hx, hw)
+        torch.cuda.synchronize()
+        for name in ("x", "werr", "wcodes"):
+            assert torch.equal(getattr(a, name), getattr(b, name)), name
+        for i in range(N):
+            assert torch.equal(a.errs[i], b.errs[i]) and torch.equal(a.codes[i], b.codes[i])
+            assert torch.equal(amw[i], bmw[i]) and torch.equal(avw[i], bvw[i]) and torch.equal(a.scales[i], b.scales[i])
+            assert np.array_equal(a.host_codes(i), out["words"][i])
+            close(rep, "err", a.errs[i].cpu().numpy(), he[i])
+            close(rep, "mw", amw[i].cpu().numpy(), hm[i])
+            close(rep, "vw", avw[i].cpu().numpy(), hv[i])
+        close(rep, "x", a.x.cpu().numpy(), hx)
+        close(rep, "werr", a.werr.cpu().numpy(), hw)
+        assert np.array_equal(a.wcodes[:P].cpu().numpy(), out["wcodes"])
+    assert q.get_status() == 0 and rep.float_not_bit_exact == 0
+    q.close()

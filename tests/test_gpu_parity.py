@@ -396,3 +396,40 @@ def test_variant_w_fused_step(N, rounding):
         assert np.array_equal(a.wcodes[:P].cpu().numpy(), out["wcodes"])
     assert q.get_status() == 0 and rep.float_not_bit_exact == 0
     q.close()
+
+
+def test_step_is_capturable_in_a_hip_graph():
+    """The compute calls only enqueue kernels (no allocation, no memset, no synchronisation), so a
+    step can be captured once and replayed; every replay must equal the eager call on a twin state."""
+    gcfg, _ = configs(k_g=2, k_x=6)
+    sizes = RAGGED + [50000]
+    seg_off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    P, N = int(seg_off[-1]), 4
+    q = QAdam(gcfg, seg_off, N)
+    gen = torch.Generator().manual_seed(11)
+    x0 = torch.randn(P, generator=gen) * 0.02
+    a, b = DeviceState(q, x0), DeviceState(q, x0)
+    for i in range(N):
+        a.grads[i].copy_(torch.randn(P, generator=gen) * 0.01)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        a.step_fused(1, 1e-3, 0.999)
+    # capture does not execute: a's state is untouched so far
+    assert torch.equal(a.x.cpu(), x0)
+    for rep in range(4):
+        for i in range(N):
+            gr = torch.randn(P, generator=gen) * 0.01
+            a.grads[i].copy_(gr); b.grads[i].copy_(gr)
+        graph.replay()
+        b.step_fused(1, 1e-3, 0.999)
+        torch.cuda.synchronize()
+        for name in ("x", "m", "v", "werr", "wcodes"):
+            assert torch.equal(getattr(a, name), getattr(b, name)), (rep, name)
+        for i in range(N):
+            assert torch.equal(a.errs[i], b.errs[i]) and torch.equal(a.codes[i], b.codes[i]), rep
+            assert torch.equal(a.scales[i], b.scales[i])
+        # eager work between replays
+        _ = (a.x * 2).sum().item()
+    assert q.get_status() == 0
+    q.close()

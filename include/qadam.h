@@ -5,15 +5,15 @@
  * The step, per parameter (notation of the paper: x iterate, m and v moments, e error-feedback
  * term, alpha_t step size, beta momentum, theta_t averaging parameter, N workers):
  *
- *   worker i :  p = g_i + e_i                         error-feedback add   (Alg. 1 line 5, Alg. 3 line 6)
+ *   worker i :  p = g_i + e_i                         error-feedback add   (Alg. 1 update step, Alg. 3 send step)
  *               s_il = ||p||_inf over layer l        scale of Q_g         (Sec. 5.1)
  *               q = Q_g(p) = s * nearest point of G  G = {0, +-2^-k_g, ..., +-1/2, +-1}   (Sec. 5.1)
- *               e_i <- p - q                          residual             (Alg. 1 line 6, Alg. 3 line 7)
- *   server   :  gbar = (1/N) sum_i q_i               mean of the messages (Alg. 2 line 3)
- *               v <- theta_t v + (1-theta_t) gbar^2   (Alg. 1 line 3)
- *               m <- beta m + (1-beta) gbar           (Alg. 1 line 4)
- *               x <- x - alpha_t m / sqrt(v + eps)    (Alg. 1 line 5 without the quantizer)
- *               x^ = Q_x(x [+ e^x]),  e^x <- (x [+ e^x]) - x^      (Sec. 5.1; Alg. 2 lines 2 and 6)
+ *               e_i <- p - q                          residual             (Alg. 1 / Alg. 3 residual step)
+ *   server   :  gbar = (1/N) sum_i q_i               mean of the messages (Alg. 2 gather step)
+ *               v <- theta_t v + (1-theta_t) gbar^2   (Alg. 1 second-moment step)
+ *               m <- beta m + (1-beta) gbar           (Alg. 1 first-moment step)
+ *               x <- x - alpha_t m / sqrt(v + eps)    (Alg. 1 update step without the quantizer)
+ *               x^ = Q_x(x [+ e^x]),  e^x <- (x [+ e^x]) - x^      (Sec. 5.1; Alg. 2 broadcast and output steps)
  *
  * This is "variant S": the workers quantize gradients and the server owns the moments.  The
  * paper's Algorithms 2-3 keep the moments on the workers and quantize the Adam update instead
@@ -159,7 +159,7 @@ int qadam_step_fused_w(qadam_handle_t h, int64_t step, float lr, float beta2,
                        float* const* errs, void* const* codes, float* const* scales,
                        float* x_dev, float* werr_dev, void* wcodes_dev, void* stream);
 
-/* Dequantize weight codes to fp32 (what a worker does with the broadcast of Alg. 2 line 2). */
+/* Dequantize weight codes to fp32 (what a worker does with the broadcast of Alg. 2). */
 int qadam_weight_dequantize(qadam_handle_t h, const void* wcodes_dev, float* xhat_dev, void* stream);
 
 /* Read (and optionally clear) the status word.  Synchronises the given stream. */

@@ -284,7 +284,7 @@ void oq_unpack_codes(int32_t bits, const uint32_t* words, int64_t n, uint8_t* co
 }
 
 /* ------------------------------------------------------------------------ */
-/* Adam core: Algorithm 1 lines 3-5 (Algorithm 3 lines 4-6)                  */
+/* Adam core: moment recursions and step of Algorithm 1 (= Algorithm 3)      */
 /* ------------------------------------------------------------------------ */
 void oq_adam_update(const oq_config* cfg, float lr, float beta2, int64_t step,
                     const float* g, float* m, float* v, float* u, int64_t n)
@@ -490,14 +490,14 @@ int oq_step_w(const oq_config* cfg, const int64_t* seg_off, int32_t L, int32_t N
     float* q = (float*)malloc(sizeof(float) * (size_t)(P > 0 ? P : 1));
     float* u = (float*)malloc(sizeof(float) * (size_t)(P > 0 ? P : 1));
     for (int32_t i = 0; i < N; ++i) {
-        /* Algorithm 3 lines 4-5: local moments; lines 6-7: delta = Q_g(u + e), e' = u + e - delta */
+        /* Algorithm 3: local moments, then delta = Q_g(u + e) and e' = u + e - delta */
         oq_adam_update(cfg, lr, beta2, step, grads[i], mw[i], vw[i], u, P);
         status |= worker_message(cfg, seg_off, L, index_base, i, step, u, errs[i],
                                  words ? words[i] : NULL, scales ? scales[i] : NULL,
                                  tie_g ? tie_g[i] : NULL, q);
         for (int64_t j = 0; j < P; ++j) acc[j] = acc[j] + q[j];
     }
-    /* Algorithm 2 lines 3-4 with the descent sign of Algorithm 1 line 5 */
+    /* Algorithm 2: mean of the messages, then the update, with the descent sign of Algorithm 1 */
     mean_of_workers(acc, N, P);
     for (int64_t j = 0; j < P; ++j) x[j] = x[j] - acc[j];
     oq_weight_quantize(cfg, P, index_base, step, x, werr, wcodes, NULL, tie_x);

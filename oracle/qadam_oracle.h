@@ -11,11 +11,11 @@
  *     G = {0, +-2^-k_g, ..., +-1/2, +-1}) and the weight quantizer Q_x
  *     (half of the nearest point of the uniform grid with spacing 2^-k_x on
  *     [-1, 1]).
- *   - Algorithm 1, lines 3-6 and Algorithm 3, lines 4-7: moment updates
+ *   - Algorithm 1 and Algorithm 3 (moment, update and residual steps): moment updates
  *     v = theta*v + (1-theta)*g^2, m = beta*m + (1-beta)*g, the step
  *     alpha*m/sqrt(v+eps) (eps inside the root, no bias correction) and the
  *     error-feedback residual e' = (value + e) - Q_g(value + e).
- *   - Algorithm 2, lines 2-4 and 6: the server averages the N worker
+ *   - Algorithm 2 (broadcast, gather, update and output steps): the server averages the N worker
  *     messages, keeps the full-precision iterate and emits Q_x of it.
  *
  * Two placements of the moments are implemented:
@@ -110,7 +110,7 @@ void oq_qx(const oq_config* cfg, const float* y, int64_t n, int64_t j0, int64_t 
 void oq_pack_codes(int32_t bits, const uint8_t* code, int64_t n, uint32_t* words);
 void oq_unpack_codes(int32_t bits, const uint32_t* words, int64_t n, uint8_t* code);
 
-/* ---- Adam core (Algorithm 1 lines 3-5 without the quantizer) ---- */
+/* ---- Adam core (moment and update steps of Algorithm 1 without the quantizer) ---- */
 /* updates m, v in place and writes the step u = alpha*m/sqrt(v+eps) (flavour 0)
  * so that the caller forms x - u or Q_g(u + e). */
 void oq_adam_update(const oq_config* cfg, float lr, float beta2, int64_t step,

@@ -1,6 +1,6 @@
 // gfx950 (MI355X, CDNA4) kernels of the Quantized-Adam-with-error-feedback step
-// (arXiv 2004.14180: Sec. 5.1 for the quantizers Q_g and Q_x, Algorithm 1 lines 3-6 for the
-// moments / step / residual, Algorithm 2 line 3 for the mean over workers).
+// (arXiv 2004.14180: Sec. 5.1 for the quantizers Q_g and Q_x, Algorithm 1 for the
+// moments / step / residual, Algorithm 2 (gather step) for the mean over workers).
 //
 // Everything here is a streaming pass bound by HBM bandwidth: no contraction, no MFMA.  The design
 // rules are the ones that matter for that regime on CDNA4:
@@ -332,7 +332,7 @@ __device__ __forceinline__ void store_wcodes(void* __restrict__ base, int wcode_
 }
 
 // ------------------------------------------------------------------------------------------------
-// Server arithmetic on one lane: moments (Alg. 1 lines 3-4) and the step alpha m / sqrt(v + eps).
+// Server arithmetic on one lane: moments (Alg. 1, moment recursions) and the step alpha m / sqrt(v + eps).
 // ------------------------------------------------------------------------------------------------
 __device__ __forceinline__ float adam_step(const StepScalars& S, float gbar, float& m, float& v)
 {

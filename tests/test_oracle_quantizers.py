@@ -118,7 +118,7 @@ def test_qx_bruteforce_argmin(oracle, k_x):
 # ------------------------------------------------- exact residual, ranges, signs
 @pytest.mark.parametrize("k_g", [0, 1, 2, 5])
 def test_qg_exact_residual_and_ranges(oracle, k_g):
-    """Error feedback (Algorithm 1 line 6): e' = p - Q_g(p).  With nearest rounding on a
+    """Error feedback (residual step of Algorithm 1): e' = p - Q_g(p).  With nearest rounding on a
     power-of-two grid p/q lies in [1/2, 2] for every non-zero code, so the fp32 subtraction is
     exact and q + e' == p bit for bit.  Codes stay in range; the arg-max element is reproduced."""
     rng = np.random.default_rng(300 + k_g)

@@ -13,7 +13,7 @@ def _zeros(n, k=1):
 
 # ------------------------------------------------------------------ closed form
 def test_constant_gradient_closed_form(oracle):
-    """Algorithm 1 lines 3-5 with Q_g = Q_x = id and a constant gradient g:
+    """Moment and update steps of Algorithm 1 with Q_g = Q_x = id and a constant gradient g:
     m_t = (1 - beta^t) g, v_t = (1 - theta^t) g^2 (unrolling the recursions from m_0 = v_0 = 0),
     x_{t+1} = x_t - alpha (1-beta^t) g / sqrt((1-theta^t) g^2 + eps): eps inside the root, no bias
     correction.  beta != theta and a large eps make swapped or misplaced constants visible."""
@@ -147,7 +147,7 @@ def test_error_feedback_telescoping_variant_s(oracle, k_g):
 def test_variant_w_telescoping(oracle):
     """Notation 3: x~_t = x_t - mean_i e_t^(i) follows the un-quantized recursion
     x~_{t+1} = x~_t + mean_i Delta_t^(i), Delta = -alpha m / sqrt(v + eps) with the workers' own
-    moments (Algorithm 3 lines 4-5).  The gradients are given, so the right-hand side is an fp64
+    moments (moment steps of Algorithm 3).  The gradients are given, so the right-hand side is an fp64
     per-worker generic Adam that never sees a quantizer."""
     n, T, N = 2048, 30, 4
     beta, theta, eps, lr = 0.9, 0.999, 1e-5, 1e-3
@@ -180,7 +180,7 @@ def test_variant_w_telescoping(oracle):
 
 
 def test_variant_s_server_mean_and_order(oracle):
-    """Algorithm 2 line 3 (mean of the N worker messages) applied to dequantized gradients: the
+    """Gather step of Algorithm 2 (mean of the N worker messages) applied to dequantized gradients: the
     server's m after one step from zero is (1-beta) * mean_i q_i, with the q_i decoded
     independently here from the packed words and scales."""
     n, N = 1500, 8

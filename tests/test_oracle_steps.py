@@ -311,3 +311,34 @@ def test_step_window_equals_step(oracle):
             assert np.array_equal(ew[i], errs[i][a:b])
             codes = oracle.unpack_all(2, segs, full["words"][i])
             assert np.array_equal(win["codes"][i], codes[a:b])
+
+
+@pytest.mark.parametrize("variant", ["s", "w"])
+def test_closed_loop_quadratic_reaches_a_neighbourhood(oracle, variant):
+    """Theorems 2-3 (qualitatively): with gradients sampled at the quantized weights Q_x(x_t), the
+    iterates reach a neighbourhood of the stationary point whose size is set by the weight grid, and
+    error feedback keeps coarse (ternary) gradient quantization from stalling the descent.
+    f(x) = 1/2 ||x - x*||^2, worker gradients = (Q_x(x) - x*) + noise."""
+    n, N, T = 256, 4, 1500
+    rng = np.random.default_rng(7)
+    xstar = rng.uniform(-0.4, 0.4, n).astype(np.float32)
+    cfg = OracleConfig(k_g=0, k_x=6, weight_ef=0, beta1=0.9, eps=1e-8)
+    x = np.zeros(n, np.float32)
+    werr = np.zeros(n, np.float32)
+    errs = _zeros(n, N)
+    m, v = _zeros(n, 2)
+    mw, vw = _zeros(n, N), _zeros(n, N)
+    xhat = np.zeros(n, np.float32)
+    d0 = np.linalg.norm(xhat - xstar)
+    for t in range(1, T + 1):
+        lr = 2e-2 / np.sqrt(t)
+        grads = [((xhat - xstar) + rng.standard_normal(n) * 0.01).astype(np.float32) for _ in range(N)]
+        if variant == "s":
+            out = oracle.step_s(cfg, [0, n], t, float(lr), 0.999, grads, errs, x, m, v, werr)
+        else:
+            out = oracle.step_w(cfg, [0, n], t, float(lr), 0.999, grads, errs, mw, vw, x, werr)
+        xhat = out["wcodes"].astype(np.float32) * np.float32(2.0 ** -7)
+        assert np.array_equal(xhat, (x - werr).astype(np.float32))        # emitted weights = Q_x(x)
+    dist = np.abs(xhat - xstar)
+    assert np.linalg.norm(xhat - xstar) < 0.05 * d0
+    assert dist.max() < 4 * 2.0 ** -7                                    # a few weight-grid steps

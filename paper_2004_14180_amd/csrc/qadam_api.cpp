@@ -195,8 +195,18 @@ int qadam_init(qadam_handle_t* out, const qadam_config_t* cfg, const int64_t* se
     h->wcode_bytes = cfg->k_x <= 6 ? 1 : 2;
     h->tile_elems = tile_elems_from_env();
 
+    // one workgroup per tile: a launch needs tiles * threads per workgroup below 2^32
+    int64_t tile_count = 0;
+    for (int l = 0; l < num_segments; ++l)
+        tile_count += (seg_offsets[l + 1] - seg_offsets[l] + h->tile_elems - 1) / h->tile_elems;
+    if (tile_count >= ((int64_t)1 << 32) / kBlockThreads) {
+        delete h;
+        return fail(QADAM_ERANGE, "too many tiles for one launch (about parameters / 4096 must stay below 2^24)");
+    }
+
     // tile table: segments cut into runs of tile_elems elements
     std::vector<Tile> tiles;
+    tiles.reserve((size_t)tile_count);
     std::vector<int32_t> seg_tile_begin(num_segments + 1, 0);
     int64_t word_off = 0;
     for (int l = 0; l < num_segments; ++l) {
@@ -218,7 +228,7 @@ int qadam_init(qadam_handle_t* out, const qadam_config_t* cfg, const int64_t* se
         word_off += seg_words;
     }
     h->code_words = word_off;
-    if (tiles.size() > (size_t)0x7fffffff) { delete h; return fail(QADAM_ERANGE, "too many tiles"); }
+
     seg_tile_begin[num_segments] = (int32_t)tiles.size();
     h->num_tiles = (int32_t)tiles.size();
 

@@ -174,14 +174,20 @@ __device__ __forceinline__ void worker_lane(const float (&g)[V], const float (&e
     }
 }
 
-// value of one code with scale s
-__device__ __forceinline__ float qg_decode(uint32_t code, float s, const QgConst& c, int mu_bits)
+// Value of the code stored at bit `pos` of a 32-element group's plane words w[0..MU_BITS]
+// (planes 0..MU_BITS-1 hold the level index mu, plane MU_BITS the sign), with layer scale s:
+// +-s * 2^(mu-1-k_g), or 0 for mu == 0.  The bits are taken straight from the words, so no
+// per-element code has to be assembled first.
+template <int MU_BITS>
+__device__ __forceinline__ float qg_decode_planes(const uint32_t (&w)[4], uint32_t pos, float s, const QgConst& c)
 {
-    const int mu = (int)(code & ((1u << mu_bits) - 1u));
-    const uint32_t sign = ((code >> mu_bits) & 1u) << 31;
-    const float lvl = u2f((uint32_t)(mu + c.ebias) << 23);
+    uint32_t mu = __builtin_amdgcn_ubfe(w[0], pos, 1u);
+#pragma unroll
+    for (int k = 1; k < MU_BITS; ++k) mu |= __builtin_amdgcn_ubfe(w[k], pos, 1u) << k;
+    const uint32_t sign = (w[MU_BITS] << (31u - pos)) & 0x80000000u;
+    const float lvl = u2f((mu + (uint32_t)c.ebias) << 23);
     float qa = s * lvl;
-    qa = mu > 0 ? qa : 0.0f;
+    qa = mu > 0u ? qa : 0.0f;
     return u2f(f2u(qa) | sign);
 }
 
@@ -237,30 +243,16 @@ __device__ __forceinline__ uint32_t pack_planes(uint32_t codes, int code_bits, i
     return sel;
 }
 
-// codes of this lane's V elements from packed words (inverse of pack_planes)
-template <int V>
-__device__ __forceinline__ uint32_t unpack_planes(const uint32_t* __restrict__ chunk_words, int code_bits, int lane)
+// plane words of the 32-element group that holds this lane's V elements, and the bit position of
+// the lane's first element in them (inverse of pack_planes)
+template <int V, int MU_BITS>
+__device__ __forceinline__ uint32_t load_planes(const uint32_t* __restrict__ chunk_words, int lane, uint32_t (&w)[4])
 {
-    uint32_t codes = 0;
-    if constexpr (V == 4) {
-        const uint32_t* gw = chunk_words + (lane >> 3) * code_bits;
-        const int sh = (lane & 7) * 4;
+    constexpr int CODE_BITS = MU_BITS + 1;
+    const uint32_t* gw = chunk_words + (V == 4 ? (lane >> 3) : (lane >> 5)) * CODE_BITS;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            if (k < code_bits) {
-                const uint32_t nib = (gw[k] >> sh) & 0xFu;
-                // spread bit j of the nibble to bit 4*j + k
-                codes |= ((nib & 1u) | ((nib & 2u) << 3) | ((nib & 4u) << 6) | ((nib & 8u) << 9)) << k;
-            }
-        }
-    } else {
-        const uint32_t* gw = chunk_words + (lane >> 5) * code_bits;
-        const int b = lane & 31;
-#pragma unroll
-        for (int k = 0; k < 4; ++k)
-            if (k < code_bits) codes |= ((gw[k] >> b) & 1u) << k;
-    }
-    return codes;
+    for (int k = 0; k < 4; ++k) w[k] = k < CODE_BITS ? gw[k] : 0u;
+    return V == 4 ? (uint32_t)(lane & 7) * 4u : (uint32_t)(lane & 31);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -628,7 +620,9 @@ struct ServerArgs {
     int apply_only;         // variant W: x <- x - mean_i q_i, no moments
 };
 
-template <int V>
+// U = number of workers whose code words are loaded together (N must be a multiple of U);
+// MU_BITS = bits of the level index (code bits minus the sign)
+template <int V, int U, int MU_BITS>
 __device__ __forceinline__ void server_tile(const ServerArgs& A, const Tile& t)
 {
     constexpr int WAVE_ELEMS = 64 * V, BLOCK_ELEMS = (kBlockThreads / 64) * WAVE_ELEMS;
@@ -641,24 +635,33 @@ __device__ __forceinline__ void server_tile(const ServerArgs& A, const Tile& t)
         if (nvalid == 0) continue;
         const int64_t gi = t.start + off;
         const int64_t cw = t.code_word + (int64_t)(base >> 5) * S.code_bits;
+        // server state first: its latency hides behind the decoding
+        float xv[V], mv[V], vv[V];
+        load_v<V>(A.x + gi, nvalid, xv);
+        if (!A.apply_only) {
+            load_v<V>(A.m + gi, nvalid, mv);
+            load_v<V>(A.v + gi, nvalid, vv);
+        }
         float acc[V];
 #pragma unroll
         for (int j = 0; j < V; ++j) acc[j] = 0.0f;
-        for (int i = 0; i < S.num_workers; ++i) {
-            const float s = A.scales[i][t.seg];
-            const uint32_t codes = unpack_planes<V>(A.codes[i] + cw, S.code_bits, lane);
+        for (int i0 = 0; i0 < S.num_workers; i0 += U) {
+            uint32_t w[U][4];
+            uint32_t pos = 0;
 #pragma unroll
-            for (int j = 0; j < V; ++j) acc[j] = acc[j] + qg_decode((codes >> (4 * j)) & 0xFu, s, c, S.mu_bits);
+            for (int u = 0; u < U; ++u) pos = load_planes<V, MU_BITS>(A.codes[i0 + u] + cw, lane, w[u]);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const float s = A.scales[i0 + u][t.seg];
+#pragma unroll
+                for (int j = 0; j < V; ++j)
+                    acc[j] = acc[j] + qg_decode_planes<MU_BITS>(w[u], pos + (uint32_t)j, s, c);
+            }
         }
-        float xv[V];
-        load_v<V>(A.x + gi, nvalid, xv);
         if (A.apply_only) {
 #pragma unroll
             for (int j = 0; j < V; ++j) xv[j] = xv[j] - mean_over_workers(S, acc[j]);
         } else {
-            float mv[V], vv[V];
-            load_v<V>(A.m + gi, nvalid, mv);
-            load_v<V>(A.v + gi, nvalid, vv);
 #pragma unroll
             for (int j = 0; j < V; ++j) {
                 const float u = adam_step(S, mean_over_workers(S, acc[j]), mv[j], vv[j]);
@@ -671,12 +674,13 @@ __device__ __forceinline__ void server_tile(const ServerArgs& A, const Tile& t)
     }
 }
 
+template <int U, int MU_BITS>
 __global__ void __launch_bounds__(kBlockThreads) k_server_step(ServerArgs A)
 {
     const int ti = blockIdx.x;
     const Tile t = A.tiles[ti];
-    if (t.flags & kTileUnaligned) server_tile<1>(A, t);
-    else server_tile<4>(A, t);
+    if (t.flags & kTileUnaligned) server_tile<1, 1, MU_BITS>(A, t);
+    else server_tile<4, U, MU_BITS>(A, t);
 }
 
 // ---- weight quantizer alone (qadam_weight_quantize) ----------------------------------------------
@@ -945,13 +949,28 @@ static void fill_server_args(ServerArgs& A, const Launch& L, const StepScalars& 
     for (int i = 0; i < QADAM_MAX_WORKERS; ++i) { A.codes[i] = W.codes[i]; A.scales[i] = W.scales[i]; }
 }
 
+static void launch_server_kernel(const Launch& L, const ServerArgs& A)
+{
+    const dim3 grid(L.num_tiles), block(kBlockThreads);
+    const bool four = A.S.num_workers % 4 == 0;
+#define QADAM_LAUNCH_SERVER(MB)                                                                       \
+    do {                                                                                              \
+        if (four) hipLaunchKernelGGL((k_server_step<4, MB>), grid, block, 0, L.stream, A);            \
+        else hipLaunchKernelGGL((k_server_step<1, MB>), grid, block, 0, L.stream, A);                 \
+    } while (0)
+    if (A.S.mu_bits == 1) QADAM_LAUNCH_SERVER(1);
+    else if (A.S.mu_bits == 2) QADAM_LAUNCH_SERVER(2);
+    else QADAM_LAUNCH_SERVER(3);
+#undef QADAM_LAUNCH_SERVER
+}
+
 hipError_t launch_server_step(const Launch& L, const StepScalars& S, const WorkerPtrs& W, const ServerPtrs& sp)
 {
     if (L.num_tiles == 0) return hipSuccess;
     ServerArgs A;
     fill_server_args(A, L, S, W);
     A.x = sp.x; A.m = sp.m; A.v = sp.v; A.apply_only = 0;
-    hipLaunchKernelGGL(k_server_step, dim3(L.num_tiles), dim3(kBlockThreads), 0, L.stream, A);
+    launch_server_kernel(L, A);
     return hipGetLastError();
 }
 
@@ -961,7 +980,7 @@ hipError_t launch_server_apply_w(const Launch& L, const StepScalars& S, const Wo
     ServerArgs A;
     fill_server_args(A, L, S, W);
     A.x = x; A.m = nullptr; A.v = nullptr; A.apply_only = 1;
-    hipLaunchKernelGGL(k_server_step, dim3(L.num_tiles), dim3(kBlockThreads), 0, L.stream, A);
+    launch_server_kernel(L, A);
     return hipGetLastError();
 }
 

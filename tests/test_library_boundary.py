@@ -54,6 +54,9 @@ def test_bad_configs_are_rejected_on_the_host(lib):
     assert init(cfg, N=33) == -3
     assert init(cfg, segs=(C.c_int64 * 3)(1, 10, 20)) == -1
     assert init(cfg, segs=(C.c_int64 * 3)(0, 30, 20)) == -1
+    # sizes beyond one launch (one workgroup per 4096-element tile, fewer than 2^24 tiles) and beyond 2^40
+    assert init(cfg, segs=(C.c_int64 * 2)(0, 1 << 36), L=1) == -3
+    assert init(cfg, segs=(C.c_int64 * 2)(0, (1 << 40) + 1), L=1) == -3
     assert lib.qadam_destroy(None) == 0
     assert lib.qadam_grad_code_bytes(None) == 0
 

@@ -159,8 +159,21 @@ int qadam_step_fused_w(qadam_handle_t h, int64_t step, float lr, float beta2,
                        float* const* errs, void* const* codes, float* const* scales,
                        float* x_dev, float* werr_dev, void* wcodes_dev, void* stream);
 
-/* Dequantize weight codes to fp32 (what a worker does with the broadcast of Alg. 2). */
+/* Dequantize weight codes (what a worker does with the broadcast of Alg. 2): x^ = j * 2^-(k_x+1).
+ *   qadam_weight_dequantize      xhat_dev [P] fp32, exact.
+ *   qadam_weight_dequantize_f16  xhat_dev [P] IEEE binary16 (2 bytes per element, 16-byte aligned), for
+ *                                a consumer that computes in half precision; exact for k_x <= 10,
+ *                                round-to-nearest-even of the fp32 value beyond (|j| needs more than
+ *                                11 significand bits). */
 int qadam_weight_dequantize(qadam_handle_t h, const void* wcodes_dev, float* xhat_dev, void* stream);
+int qadam_weight_dequantize_f16(qadam_handle_t h, const void* wcodes_dev, void* xhat_dev, void* stream);
+
+/* Diagnostic: per-layer squared Euclidean norms  out[l] = sum_{j in layer l} (a_j + b_j)^2, with the sum
+ * a_j + b_j taken in fp32 (as the step forms g + e) and squares and sums in fp64 in a fixed order, so the
+ * result is the same bits on every run.  b_dev may be NULL (then a alone).  out_dev: L doubles (device).
+ * Called with (g_i, e_i) before a step and with (e_i, NULL) after it, the ratio of the two is the
+ * empirical ||p - Q_g(p)||^2 / ||p||^2 of Assumption 2 (must stay below 1). */
+int qadam_layer_sumsq(qadam_handle_t h, const float* a_dev, const float* b_dev, double* out_dev, void* stream);
 
 /* Read (and optionally clear) the status word.  Synchronises the given stream. */
 int qadam_get_status(qadam_handle_t h, qadam_status_t* out, int32_t clear, void* stream);

@@ -22,6 +22,7 @@ EXPORTS = [
     "qadam_init", "qadam_destroy", "qadam_grad_code_bytes", "qadam_weight_code_bytes",
     "qadam_num_params", "qadam_worker_quantize", "qadam_server_step", "qadam_weight_quantize",
     "qadam_step_fused", "qadam_worker_step_w", "qadam_server_apply_w", "qadam_step_fused_w", "qadam_weight_dequantize",
+    "qadam_weight_dequantize_f16", "qadam_layer_sumsq",
     "qadam_get_status", "qadam_last_error", "qadam_profile_enable", "qadam_profile_read",
 ]
 
@@ -94,6 +95,8 @@ def load_library():
                                        C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), vp, vp, vp, vp]
     lib.qadam_server_apply_w.argtypes = [vp, i64, C.POINTER(vp), C.POINTER(vp), vp, vp]
     lib.qadam_weight_dequantize.argtypes = [vp, vp, vp, vp]
+    lib.qadam_weight_dequantize_f16.argtypes = [vp, vp, vp, vp]
+    lib.qadam_layer_sumsq.argtypes = [vp, vp, vp, vp, vp]
     lib.qadam_get_status.argtypes = [vp, C.POINTER(_Status), i32, vp]
     lib.qadam_last_error.restype = C.c_char_p
     lib.qadam_profile_enable.argtypes = [vp, i32]
@@ -209,6 +212,13 @@ class QAdam:
 
     def weight_dequantize(self, wcodes, xhat, stream=None):
         self._check(self._lib.qadam_weight_dequantize(self._h, _ptr(wcodes), _ptr(xhat), _stream(stream)))
+
+    def weight_dequantize_f16(self, wcodes, xhat_half, stream=None):
+        self._check(self._lib.qadam_weight_dequantize_f16(self._h, _ptr(wcodes), _ptr(xhat_half), _stream(stream)))
+
+    def layer_sumsq(self, a, b, out, stream=None):
+        """out[l] = sum over layer l of (a + b)^2 in fp64 (b may be None)."""
+        self._check(self._lib.qadam_layer_sumsq(self._h, _ptr(a), _ptr(b), _ptr(out), _stream(stream)))
 
     def profile_enable(self, on=True):
         self._check(self._lib.qadam_profile_enable(self._h, int(on)))

@@ -26,6 +26,7 @@ struct qadam_ctx {
     float*    d_inv_scales;     // [num_workers][num_segments]
     uint32_t* d_tile_max;       // [num_workers][num_tiles]
     int32_t*  d_seg_tile_begin; // [num_segments + 1]
+    double*   d_tile_sum;       // [num_tiles]
     bool       profile;
     bool       profile_valid;
     hipEvent_t ev[3];
@@ -108,7 +109,7 @@ Launch make_launch(const qadam_ctx* h, void* stream)
 {
     Launch L;
     L.tiles = h->d_tiles; L.inv_scales = h->d_inv_scales;
-    L.tile_max = h->d_tile_max; L.seg_tile_begin = h->d_seg_tile_begin;
+    L.tile_max = h->d_tile_max; L.seg_tile_begin = h->d_seg_tile_begin; L.tile_sum = h->d_tile_sum;
     L.num_tiles = h->num_tiles; L.num_segments = h->num_segments;
     L.num_params = h->num_params; L.status = h->d_status; L.stream = static_cast<hipStream_t>(stream);
     return L;
@@ -242,6 +243,8 @@ int qadam_init(qadam_handle_t* out, const qadam_config_t* cfg, const int64_t* se
         e = hipMemcpy(h->d_seg_tile_begin, seg_tile_begin.data(), sizeof(int32_t) * (num_segments + 1), hipMemcpyHostToDevice);
     if (e == hipSuccess && h->num_tiles > 0)
         e = hipMalloc(reinterpret_cast<void**>(&h->d_tile_max), sizeof(uint32_t) * (size_t)h->num_tiles * num_workers);
+    if (e == hipSuccess && h->num_tiles > 0)
+        e = hipMalloc(reinterpret_cast<void**>(&h->d_tile_sum), sizeof(double) * (size_t)h->num_tiles);
     if (e == hipSuccess && h->num_tiles > 0) {
         e = hipMalloc(reinterpret_cast<void**>(&h->d_tiles), sizeof(Tile) * tiles.size());
         if (e == hipSuccess)
@@ -253,6 +256,7 @@ int qadam_init(qadam_handle_t* out, const qadam_config_t* cfg, const int64_t* se
         if (h->d_inv_scales) (void)hipFree(h->d_inv_scales);
         if (h->d_tile_max) (void)hipFree(h->d_tile_max);
         if (h->d_seg_tile_begin) (void)hipFree(h->d_seg_tile_begin);
+        if (h->d_tile_sum) (void)hipFree(h->d_tile_sum);
         delete h;
         return hip_fail(e, "qadam_init device tables");
     }
@@ -270,6 +274,7 @@ int qadam_destroy(qadam_handle_t h)
     if (h->d_inv_scales) (void)hipFree(h->d_inv_scales);
     if (h->d_tile_max) (void)hipFree(h->d_tile_max);
     if (h->d_seg_tile_begin) (void)hipFree(h->d_seg_tile_begin);
+    if (h->d_tile_sum) (void)hipFree(h->d_tile_sum);
     delete h;
     return QADAM_OK;
 }
@@ -341,7 +346,18 @@ int qadam_weight_dequantize(qadam_handle_t h, const void* wcodes_dev, float* xha
     QADAM_CHECK(check_ptr(wcodes_dev, "wcodes_dev", !empty));
     QADAM_CHECK(check_ptr(xhat_dev, "xhat_dev", !empty));
     const StepScalars S = make_scalars(h, 1, 0.0f, 0.0f);
-    QADAM_HIP(launch_weight_dequantize(make_launch(h, stream), S, wcodes_dev, xhat_dev));
+    QADAM_HIP(launch_weight_dequantize(make_launch(h, stream), S, wcodes_dev, xhat_dev, false));
+    return QADAM_OK;
+}
+
+int qadam_weight_dequantize_f16(qadam_handle_t h, const void* wcodes_dev, void* xhat_dev, void* stream)
+{
+    QADAM_CHECK(check_handle(h));
+    const bool empty = h->num_params == 0;
+    QADAM_CHECK(check_ptr(wcodes_dev, "wcodes_dev", !empty));
+    QADAM_CHECK(check_ptr(xhat_dev, "xhat_dev", !empty));
+    const StepScalars S = make_scalars(h, 1, 0.0f, 0.0f);
+    QADAM_HIP(launch_weight_dequantize(make_launch(h, stream), S, wcodes_dev, xhat_dev, true));
     return QADAM_OK;
 }
 
@@ -451,6 +467,16 @@ int qadam_server_apply_w(qadam_handle_t h, int64_t step, const void* const* code
     QADAM_CHECK(check_ptr(x_dev, "x_dev", h->num_params != 0));
     const StepScalars S = make_scalars(h, step, 0.0f, 0.0f);
     QADAM_HIP(launch_server_apply_w(make_launch(h, stream), S, W, x_dev));
+    return QADAM_OK;
+}
+
+int qadam_layer_sumsq(qadam_handle_t h, const float* a_dev, const float* b_dev, double* out_dev, void* stream)
+{
+    QADAM_CHECK(check_handle(h));
+    QADAM_CHECK(check_ptr(a_dev, "a_dev", h->num_params != 0));
+    QADAM_CHECK(check_ptr(b_dev, "b_dev", false));
+    QADAM_CHECK(check_ptr(out_dev, "out_dev", h->num_segments > 0));
+    QADAM_HIP(launch_layer_sumsq(make_launch(h, stream), a_dev, b_dev, out_dev));
     return QADAM_OK;
 }
 

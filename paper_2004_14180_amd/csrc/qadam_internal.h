@@ -68,6 +68,7 @@ struct Launch {
     int32_t     num_tiles;
     int32_t     num_segments;
     int64_t     num_params;
+    double*     tile_sum;   // device, [num_tiles]: per-tile partial sums of the norm diagnostic
     uint32_t*   status;     // device status word
     hipStream_t stream;
 };
@@ -80,8 +81,9 @@ hipError_t launch_reduce_scales(const Launch& L, const WorkerPtrs& W, int first_
 hipError_t launch_worker_quantize(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int worker);
 hipError_t launch_server_step(const Launch& L, const StepScalars& S, const WorkerPtrs& W, const ServerPtrs& sp);
 hipError_t launch_weight_quantize(const Launch& L, const StepScalars& S, const float* x, float* werr, void* wcodes);
-hipError_t launch_weight_dequantize(const Launch& L, const StepScalars& S, const void* wcodes, float* xhat);
+hipError_t launch_weight_dequantize(const Launch& L, const StepScalars& S, const void* wcodes, void* xhat, bool half);
 hipError_t launch_fused(const Launch& L, const StepScalars& S, const WorkerPtrs& W, const ServerPtrs& sp);
+hipError_t launch_layer_sumsq(const Launch& L, const float* a, const float* b, double* out);
 // variant W
 hipError_t launch_worker_moments_w(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker, int num);
 hipError_t launch_fused_w(const Launch& L, const StepScalars& S, const WorkerPtrs& W, const ServerPtrs& sp);

@@ -25,6 +25,7 @@
 //     selects the grid level is taken as p * (1/s) and redone with the IEEE division only when it
 //     lands within 8 ulp of a decision threshold, which cannot change any decision (the product
 //     is within 2.5 ulp of the correctly rounded quotient).
+#include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 
 #include "qadam_internal.h"
@@ -713,19 +714,22 @@ __global__ void __launch_bounds__(kBlockThreads) k_weight_quantize(WeightArgs A)
 
 struct DequantArgs {
     const void* wcodes;
-    float* xhat;
+    void* xhat;             // float or __half, per the kernel's template argument
     int64_t n;
     int wcode_bytes;
     float inv_two_kx1;
 };
 
+template <bool HALF>
 __global__ void __launch_bounds__(kBlockThreads) k_weight_dequantize(DequantArgs A)
 {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < A.n;
          i += (int64_t)gridDim.x * blockDim.x) {
         const int j = A.wcode_bytes == 1 ? (int)static_cast<const int8_t*>(A.wcodes)[i]
                                          : (int)static_cast<const int16_t*>(A.wcodes)[i];
-        A.xhat[i] = (float)j * A.inv_two_kx1;
+        const float xh = (float)j * A.inv_two_kx1;
+        if constexpr (HALF) static_cast<__half*>(A.xhat)[i] = __float2half_rn(xh);
+        else static_cast<float*>(A.xhat)[i] = xh;
     }
 }
 
@@ -884,6 +888,80 @@ __global__ void __launch_bounds__(kBlockThreads) k_moments_w(MomentsWArgs A)
     if (threadIdx.x == 0) A.tile_max[(size_t)w * A.num_tiles + ti] = bm;
 }
 
+// ---- diagnostic: per-layer sum of squares in fp64, fixed order ---------------------------------
+struct SumsqArgs {
+    const Tile* tiles;
+    const float* a;
+    const float* b;         // may be null
+    double* tile_sum;       // [num_tiles]
+    const int32_t* seg_tile_begin;
+    double* out;            // [num_segments]
+};
+
+// block-wide sum in a fixed order: butterfly inside each wavefront, then the wavefronts in index
+// order; every thread gets the result
+__device__ __forceinline__ double block_sum_f64(double v)
+{
+    __shared__ double wave_part[kBlockThreads / 64];
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    __syncthreads();                       // the array may still be read from an earlier call
+    if (lane == 0) wave_part[wave] = v;
+    __syncthreads();
+    double s = wave_part[0];
+#pragma unroll
+    for (int w = 1; w < kBlockThreads / 64; ++w) s += wave_part[w];
+    return s;
+}
+
+template <int V>
+__device__ __forceinline__ double sumsq_tile(const float* __restrict__ a, const float* __restrict__ b, const Tile& t)
+{
+    constexpr int BLOCK_ELEMS = kBlockThreads * V;
+    double local = 0.0;
+    for (int off = threadIdx.x * V; off < t.len; off += BLOCK_ELEMS) {
+        const int nvalid = min(t.len - off, V);
+        float av[V], bv[V];
+        load_v<V>(a + t.start + off, nvalid, av);
+        if (b) {
+            load_v<V>(b + t.start + off, nvalid, bv);
+        } else {
+#pragma unroll
+            for (int j = 0; j < V; ++j) bv[j] = 0.0f;
+        }
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            const double p = (double)(av[j] + bv[j]);     // the sum in fp32, as the step forms it
+            local += p * p;                               // exact product of two 24-bit significands
+        }
+    }
+    return local;
+}
+
+// grid: tiles
+__global__ void __launch_bounds__(kBlockThreads) k_sumsq_tiles(SumsqArgs A)
+{
+    const int ti = blockIdx.x;
+    const Tile t = A.tiles[ti];
+    double local;
+    if (t.flags & kTileUnaligned) local = sumsq_tile<1>(A.a, A.b, t);
+    else local = sumsq_tile<4>(A.a, A.b, t);
+    const double s = block_sum_f64(local);
+    if (threadIdx.x == 0) A.tile_sum[ti] = s;
+}
+
+// grid: layers.  Thread k adds tiles k, k+256, ... of its layer in that order, then the block sum.
+__global__ void __launch_bounds__(kBlockThreads) k_sumsq_layers(SumsqArgs A)
+{
+    const int l = blockIdx.x;
+    const int t0 = A.seg_tile_begin[l], t1 = A.seg_tile_begin[l + 1];
+    double local = 0.0;
+    for (int t = t0 + threadIdx.x; t < t1; t += kBlockThreads) local += A.tile_sum[t];
+    const double s = block_sum_f64(local);
+    if (threadIdx.x == 0) A.out[l] = s;
+}
+
 int grid_for(int64_t work_items, int per_block)
 {
     int64_t blocks = (work_items + per_block - 1) / per_block;
@@ -995,7 +1073,7 @@ hipError_t launch_weight_quantize(const Launch& L, const StepScalars& S, const f
     return hipGetLastError();
 }
 
-hipError_t launch_weight_dequantize(const Launch& L, const StepScalars& S, const void* wcodes, float* xhat)
+hipError_t launch_weight_dequantize(const Launch& L, const StepScalars& S, const void* wcodes, void* xhat, bool half)
 {
     if (L.num_params == 0) return hipSuccess;
     DequantArgs A;
@@ -1003,8 +1081,9 @@ hipError_t launch_weight_dequantize(const Launch& L, const StepScalars& S, const
     union { uint32_t u; float f; } cv;
     cv.u = (uint32_t)(127 - S.k_x - 1) << 23;
     A.inv_two_kx1 = cv.f;
-    hipLaunchKernelGGL(k_weight_dequantize, dim3(grid_for(L.num_params, kBlockThreads)), dim3(kBlockThreads), 0,
-                       L.stream, A);
+    const dim3 grid(grid_for(L.num_params, kBlockThreads)), block(kBlockThreads);
+    if (half) hipLaunchKernelGGL(k_weight_dequantize<true>, grid, block, 0, L.stream, A);
+    else hipLaunchKernelGGL(k_weight_dequantize<false>, grid, block, 0, L.stream, A);
     return hipGetLastError();
 }
 
@@ -1045,6 +1124,17 @@ hipError_t launch_fused(const Launch& L, const StepScalars& S, const WorkerPtrs&
 hipError_t launch_fused_w(const Launch& L, const StepScalars& S, const WorkerPtrs& W, const ServerPtrs& sp)
 {
     return launch_fused_any(L, S, W, sp, true);
+}
+
+hipError_t launch_layer_sumsq(const Launch& L, const float* a, const float* b, double* out)
+{
+    if (L.num_segments == 0) return hipSuccess;
+    SumsqArgs A;
+    A.tiles = L.tiles; A.a = a; A.b = b; A.tile_sum = L.tile_sum; A.seg_tile_begin = L.seg_tile_begin; A.out = out;
+    if (L.num_tiles > 0)
+        hipLaunchKernelGGL(k_sumsq_tiles, dim3(L.num_tiles), dim3(kBlockThreads), 0, L.stream, A);
+    hipLaunchKernelGGL(k_sumsq_layers, dim3(L.num_segments), dim3(kBlockThreads), 0, L.stream, A);
+    return hipGetLastError();
 }
 
 hipError_t launch_worker_moments_w(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker, int num)

@@ -301,6 +301,29 @@ def test_weight_dequantize_roundtrip():
     q.close()
 
 
+@pytest.mark.parametrize("k_x", [6, 10, 14])
+def test_weight_dequantize_half_precision(k_x):
+    """binary16 output: exact up to k_x = 10 (|j| <= 1024 fits 11 significand bits), round to nearest
+    even of the fp32 value beyond; checked against numpy's float32 -> float16 conversion."""
+    gcfg, ocfg = configs(k_x=k_x)
+    P = 70001
+    q = QAdam(gcfg, [0, P], 1)
+    x = ((torch.rand(P, generator=torch.Generator().manual_seed(k_x)) - 0.5) * 1.1).cuda()
+    werr = torch.zeros(P, device="cuda")
+    wc = torch.zeros(P, dtype=torch.int8 if k_x <= 6 else torch.int16, device="cuda")
+    xh = torch.zeros(P, dtype=torch.float16, device="cuda")
+    q.weight_quantize(1, x, werr, wc)
+    q.weight_dequantize_f16(wc, xh)
+    torch.cuda.synchronize()
+    want32 = oracle.qx(ocfg, x.cpu().numpy())[1]
+    want16 = want32.astype(np.float16)
+    got = xh.cpu().numpy()
+    assert np.array_equal(got, want16)          # as values: the sign of a zero is not part of x^
+    if k_x <= 10:
+        assert np.array_equal(got.astype(np.float32), want32)
+    q.close()
+
+
 # ------------------------------------------------------------- variant W (Algorithms 2-3 as printed)
 @pytest.mark.parametrize("rounding", [0, 1])
 def test_variant_w_worker_moments(rounding):
@@ -431,5 +454,94 @@ def test_step_is_capturable_in_a_hip_graph():
             assert torch.equal(a.scales[i], b.scales[i])
         # eager work between replays
         _ = (a.x * 2).sum().item()
+    assert q.get_status() == 0
+    q.close()
+
+
+@pytest.mark.parametrize("rounding", [0, 1])
+def test_checkpoint_and_resume_is_bit_identical(rounding):
+    """The complete state of the method is (x, m, v, e^x, e_1..e_N, t): all caller-owned buffers.
+    Ten steps in one go equal five steps, a copy of those buffers to the host, a NEW handle with new
+    device buffers restored from the copy, and five more steps -- bit for bit, also with stochastic
+    rounding (its random stream is a function of seed, step, worker and index only)."""
+    gcfg, _ = configs(k_g=2, k_x=6, rounding=rounding, seed=99)
+    sizes = RAGGED + [30000]
+    seg_off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    P, N = int(seg_off[-1]), 3
+    gen = torch.Generator().manual_seed(5)
+    x0 = torch.randn(P, generator=gen) * 0.02
+    grads = [[torch.randn(P, generator=gen) * 0.01 for _ in range(N)] for _ in range(10)]
+
+    def run(ds, t0, t1):
+        for t in range(t0, t1 + 1):
+            for i in range(N):
+                ds.grads[i].copy_(grads[t - 1][i])
+            ds.step_fused(t, 1e-3 / np.sqrt(t), 1.0 - 0.5 / t)     # Assumption 4 style schedules
+
+    q1 = QAdam(gcfg, seg_off, N)
+    full = DeviceState(q1, x0)
+    run(full, 1, 10)
+    q2 = QAdam(gcfg, seg_off, N)
+    first = DeviceState(q2, x0)
+    run(first, 1, 5)
+    torch.cuda.synchronize()
+    saved = dict(x=first.x.cpu(), m=first.m.cpu(), v=first.v.cpu(), werr=first.werr.cpu(),
+                 errs=[e.cpu() for e in first.errs])
+    del first
+    q2.close()
+    q3 = QAdam(gcfg, seg_off, N)
+    second = DeviceState(q3, saved["x"])
+    second.m.copy_(saved["m"]); second.v.copy_(saved["v"]); second.werr.copy_(saved["werr"])
+    for i in range(N):
+        second.errs[i].copy_(saved["errs"][i])
+    run(second, 6, 10)
+    torch.cuda.synchronize()
+    for name in ("x", "m", "v", "werr", "wcodes"):
+        assert torch.equal(getattr(full, name), getattr(second, name)), name
+    for i in range(N):
+        assert torch.equal(full.errs[i], second.errs[i]) and torch.equal(full.codes[i], second.codes[i])
+        assert torch.equal(full.scales[i], second.scales[i])
+    assert q1.get_status() == 0 and q3.get_status() == 0
+    q1.close(); q3.close()
+
+
+def test_layer_sumsq_and_assumption2_on_device():
+    """qadam_layer_sumsq: fp64 per-layer sums in a fixed order (same bits on every run), equal to a
+    plain fp64 sum within accumulation error; used before and after a step it gives the empirical
+    ||p - Q_g(p)||^2 / ||p||^2 of Assumption 2, which must stay below 1 in every layer."""
+    gcfg, _ = configs(k_g=2, k_x=6)
+    sizes = RAGGED + [1 << 20, 300000]
+    seg_off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    L, P, N = len(sizes), int(seg_off[-1]), 2
+    q = QAdam(gcfg, seg_off, N)
+    gen = torch.Generator().manual_seed(21)
+    x0 = torch.randn(P, generator=gen) * 0.02
+    ds = DeviceState(q, x0)
+    for i in range(N):
+        ds.grads[i].copy_(torch.randn(P, generator=gen) * 0.01)
+        ds.errs[i].copy_(torch.randn(P, generator=gen) * 0.002)
+    before = [torch.zeros(L, dtype=torch.float64, device="cuda") for _ in range(N)]
+    again = torch.zeros(L, dtype=torch.float64, device="cuda")
+    after = [torch.zeros(L, dtype=torch.float64, device="cuda") for _ in range(N)]
+    for i in range(N):
+        q.layer_sumsq(ds.grads[i], ds.errs[i], before[i])
+    q.layer_sumsq(ds.grads[0], ds.errs[0], again)
+    torch.cuda.synchronize()
+    assert torch.equal(before[0], again)                       # fixed order: bit-identical reruns
+    p_host = [(ds.grads[i] + ds.errs[i]).cpu().numpy().astype(np.float64) for i in range(N)]
+    ds.step_fused(1, 1e-3, 0.999)
+    for i in range(N):
+        q.layer_sumsq(ds.errs[i], None, after[i])
+    torch.cuda.synchronize()
+    for i in range(N):
+        e_host = ds.errs[i].cpu().numpy().astype(np.float64)
+        b, a = before[i].cpu().numpy(), after[i].cpu().numpy()
+        for l in range(L):
+            lo, hi = int(seg_off[l]), int(seg_off[l + 1])
+            want_b = float(np.sum(p_host[i][lo:hi] ** 2))
+            want_a = float(np.sum(e_host[lo:hi] ** 2))
+            assert abs(b[l] - want_b) <= 1e-12 * want_b and abs(a[l] - want_a) <= 1e-12 * max(want_a, 1e-300), (i, l)
+            if hi > lo:
+                assert a[l] < b[l], "Assumption 2 violated in layer %d of worker %d" % (l, i)
     assert q.get_status() == 0
     q.close()

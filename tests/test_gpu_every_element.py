@@ -1,0 +1,195 @@
+"""GPU check of EVERY element at the full size of the benchmark workload (config 5: 1 315 723 264
+parameters, 292 layers, 8 workers) and of config 4 (2^28 parameters, 16 workers), in the launch
+configuration the benchmark times.
+
+The CPU oracle can only follow samples at this size (tests/test_gpu_full_size.py).  Here the whole
+output of one qadam_step_fused call is checked against properties that hold at any size and that
+need no oracle, evaluated with plain torch tensor operations on the device (no code of the library):
+
+  worker i, layer l (Sec. 5.1 quantizer Q_g, residual step of Alg. 1 / Alg. 3):
+    * the scale is exactly max |g + e| over the layer;
+    * the stored codes are in range (level index <= k_g + 1, no "negative zero"), padding bits are 0;
+    * decoding the stored codes with the stored scale gives q with q + e' == g + e in every bit
+      (the residual is exact, so nothing of the gradient is ever lost);
+    * q is a nearest grid point: no other point of G is closer to (g + e) / s;
+  server (gather step of Alg. 2, moment recursions and update step of Alg. 1, Q_x of Sec. 5.1):
+    * m, v, x equal the same fp32 formulas evaluated with torch on the decoded messages
+      (within 1e-6 relative / 1e-7 absolute; bit differences are counted and reported);
+    * the weight codes are the nearest grid index of x + e^x (halves away from zero, saturated),
+      code * 2^-(k_x+1) + new e^x == x + old e^x exactly, and the new e^x is at most half a grid
+      step wherever x + e^x lies inside [-1/2, 1/2] (Assumption 3).
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2004_14180_amd import QAdam, QAdamConfig
+from paper_2004_14180_amd.workloads import make_workload
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _mu_bits(k_g):
+    w = 0
+    while (1 << w) < k_g + 2:
+        w += 1
+    return w
+
+
+def _segment_words(bits, n):
+    words = (n + 31) // 32 * bits
+    return (words + 3) // 4 * 4
+
+
+def decode_layer(words, n, k_g, s):
+    """Level index, sign and value of the n codes of one layer from its packed words (int32 tensor):
+    group g of 32 elements = `bits` consecutive words, word k = bit k of the codes, bit b = element b."""
+    mb = _mu_bits(k_g)
+    bits = mb + 1
+    groups = (n + 31) // 32
+    w = words[: groups * bits].view(groups, bits)
+    shifts = torch.arange(32, device=words.device, dtype=torch.int32)
+    plane = lambda k: ((w[:, k:k + 1] >> shifts) & 1).reshape(-1)
+    mu = plane(0)
+    for k in range(1, mb):
+        mu = mu | (plane(k) << k)
+    neg = plane(mb)
+    pad_ok = bool((mu[n:] == 0).all()) and bool((neg[n:] == 0).all()) and \
+        bool((words[groups * bits: _segment_words(bits, n)] == 0).all())
+    mu, neg = mu[:n], neg[:n]
+    lvl = torch.ldexp(torch.ones((), device=words.device), mu - 1 - k_g)       # 2^(mu-1-k_g), exact
+    q = torch.where(mu > 0, s * lvl, torch.zeros((), device=words.device))
+    q = torch.where(neg > 0, -q, q)
+    return mu, neg, q, pad_ok
+
+
+def check_worker_layer(k_g, p, e_new, words, s_dev, name):
+    n = p.numel()
+    if n == 0:
+        return 0
+    s_want = p.abs().max()
+    assert torch.equal(s_dev, s_want), "%s: scale %r != max|g+e| %r" % (name, float(s_dev), float(s_want))
+    mu, neg, q, pad_ok = decode_layer(words, n, k_g, s_dev)
+    assert pad_ok, name + ": padding bits"
+    assert int(mu.max()) <= k_g + 1 and not bool(((mu == 0) & (neg > 0)).any()), name + ": code range"
+    assert torch.equal(q + e_new, p), name + ": q + e' != g + e"
+    assert bool((torch.sign(q) * torch.sign(p) >= 0).all()), name + ": sign"
+    if float(s_dev) > 0:
+        # nearest point: distance to the chosen level against the distance to every level (fp64);
+        # slack of 2^-22 covers the rounding of (g+e)/s
+        a = (p.double() / s_dev.double()).abs()
+        levels = torch.tensor([0.0] + [2.0 ** (c - 1 - k_g) for c in range(1, k_g + 2)], dtype=torch.float64,
+                              device=p.device)
+        chosen = (a - levels[mu.long()]).abs()
+        best = (a.unsqueeze(1) - levels.unsqueeze(0)).abs().min(dim=1).values if n <= (1 << 24) else None
+        if best is None:
+            best = torch.full_like(a, float("inf"))
+            for c in range(levels.numel()):
+                best = torch.minimum(best, (a - levels[c]).abs())
+        assert bool((chosen <= best + 2.0 ** -22).all()), name + ": not a nearest grid point"
+    return n
+
+
+def close_count(name, got, want):
+    """1e-6 relative / 1e-7 absolute; returns the number of elements that differ in any bit."""
+    if torch.equal(got, want):
+        return 0
+    diff = got != want
+    err = (got.double() - want.double()).abs()
+    tol = 1e-7 + 1e-6 * want.double().abs()
+    assert bool((err <= tol).all()), "%s: %d elements outside tolerance" % (name, int((err > tol).sum()))
+    return int(diff.sum())
+
+
+def run_every_element(config, step):
+    wl = make_workload(config)
+    dev = torch.device("cuda:0")
+    P, N, k_g, k_x = wl.num_params, wl.num_workers, wl.k_g, wl.k_x
+    seg = wl.seg_offsets
+    L = len(seg) - 1
+    cfg = QAdamConfig(k_g=k_g, k_x=k_x, rounding=0, weight_ef=1, beta1=wl.beta1, eps=wl.eps)
+    q = QAdam(cfg, seg, N)
+    st = wl.synthetic_state(dev)
+    errs, m, v, werr = st["errs"], st["m"], st["v"], st["werr"]
+    x = wl.init_weights(dev)
+    grads = [torch.empty(P, dtype=torch.float32, device=dev) for _ in range(N)]
+    wl.fill_gradients(step, grads)
+    codes = [torch.full((q.grad_code_bytes() // 4,), -1, dtype=torch.int32, device=dev) for _ in range(N)]
+    scales = [torch.full((L,), -1.0, dtype=torch.float32, device=dev) for _ in range(N)]
+    wcodes = torch.full((P,), -1, dtype=torch.int8 if k_x <= 6 else torch.int16, device=dev)
+    # p_i = g_i + e_i before the step (the error buffers change in place), and the old server state
+    ps = [grads[i] + errs[i] for i in range(N)]
+    x0, m0, v0, w0 = x.clone(), m.clone(), v.clone(), werr.clone()
+    torch.cuda.synchronize()
+    _say("config %d: inputs ready" % config)
+    q.step_fused(step, wl.lr, wl.beta2, grads, errs, codes, scales, x, m, v, werr, wcodes)
+    torch.cuda.synchronize()
+    assert q.get_status() == 0
+    del grads
+
+    bits = _mu_bits(k_g) + 1
+    word_off = [0]
+    for l in range(L):
+        word_off.append(word_off[-1] + _segment_words(bits, seg[l + 1] - seg[l]))
+    assert word_off[-1] * 4 == q.grad_code_bytes()
+    acc = torch.zeros(P, dtype=torch.float32, device=dev)
+    checked = 0
+    for i in range(N):
+        qi = torch.empty(P, dtype=torch.float32, device=dev)
+        for l in range(L):
+            a, b = seg[l], seg[l + 1]
+            if b == a:
+                continue
+            words = codes[i][word_off[l]:word_off[l + 1]]
+            checked += check_worker_layer(k_g, ps[i][a:b], errs[i][a:b], words, scales[i][l],
+                                          "worker %d layer %d" % (i, l))
+            qi[a:b] = decode_layer(words, b - a, k_g, scales[i][l])[2]
+        acc = acc + qi                     # worker order, one fp32 rounding per addition
+        ps[i] = None
+        del qi
+        _say("config %d: worker %d/%d ok" % (config, i + 1, N))
+
+    # server: gather step of Alg. 2 on the decoded messages, moments and update step of Alg. 1
+    f32 = lambda val: float(np.float32(val))
+    beta1, beta2, lr, eps = f32(wl.beta1), f32(wl.beta2), f32(wl.lr), f32(wl.eps)
+    omb1, omb2 = f32(np.float32(1) - np.float32(wl.beta1)), f32(np.float32(1) - np.float32(wl.beta2))
+    gbar = acc / N
+    del acc
+    v1 = (v0 * beta2) + ((gbar * gbar) * omb2)
+    m1 = (m0 * beta1) + (gbar * omb1)
+    x1 = x0 - (m1 * lr) / torch.sqrt(v1 + eps)
+    del gbar, v0, m0, x0
+    bitdiff = close_count("v", v, v1) + close_count("m", m, m1) + close_count("x", x, x1)
+    del v1, m1, x1
+    # Q_x of Sec. 5.1 on the library's own x (so a tolerated rounding difference above cannot move a code)
+    y = x + w0
+    u = y * float(2 ** (k_x + 1))
+    t = torch.trunc(u)
+    j = torch.where((u - t).abs() >= 0.5, t + torch.sign(u), t)       # halves away from zero; all exact
+    j = j.clamp(-float(2 ** k_x), float(2 ** k_x))
+    assert torch.equal(wcodes.to(torch.float32), j), "weight codes"
+    assert torch.equal(j * float(2.0 ** -(k_x + 1)) + werr, y), "x^ + e^x' != x + e^x"
+    # Assumption 3 inside the grid's range (the synthetic state has a few |x| > 1/2, which saturate)
+    inside = y.abs() <= 0.5
+    assert bool((werr.abs() <= 2.0 ** -(k_x + 2))[inside].all()), "weight residual beyond half a grid step"
+    assert float(inside.float().mean()) > 0.99
+    q.close()
+    return checked, bitdiff
+
+
+def test_config5_every_element():
+    checked, bitdiff = run_every_element(5, step=3)
+    _say("config 5: %d worker-elements checked, %d server floats differ in a bit from the torch formulas"
+         % (checked, bitdiff))
+    assert checked == 8 * 1315723264
+
+
+def test_config4_every_element():
+    checked, bitdiff = run_every_element(4, step=2)
+    _say("config 4: %d worker-elements checked, %d server floats differ in a bit from the torch formulas"
+         % (checked, bitdiff))
+    assert checked == 16 * (1 << 28)

@@ -33,6 +33,15 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def build_selftest() -> str:
+    """Compile the memory-safety driver (sanitize_selftest.c) plainly, as a does-it-build check; the
+    sanitizer run itself is tests/test_oracle_sanitizers.py."""
+    exe = os.path.join(_HERE, "sanitize_selftest.bin")
+    subprocess.check_call(["gcc", "-O1", "-std=c11", "-ffp-contract=off", "-o", exe,
+                           os.path.join(_HERE, "sanitize_selftest.c"), _SRC, "-lm"])
+    return exe
+
+
 class _Cfg(C.Structure):
     _fields_ = [("k_g", C.c_int32), ("k_x", C.c_int32), ("rounding", C.c_int32),
                 ("weight_ef", C.c_int32), ("adam_flavor", C.c_int32),

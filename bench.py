@@ -89,6 +89,31 @@ def condition_allocator(nbytes_list, cycles, device):
     torch.cuda.synchronize()
 
 
+def measure_ceilings(dev):
+    """Plain torch streams over 6 GiB, best of 5, HIP events on torch's current stream."""
+    import torch
+    n = (6 << 30) // 4
+    t = torch.zeros(n, dtype=torch.float32, device=dev)
+    half = n // 2
+
+    def best(fn):
+        ms = []
+        for _ in range(5):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(); fn(); b.record()
+            torch.cuda.synchronize()
+            ms.append(a.elapsed_time(b))
+        return min(ms)
+
+    inplace = best(lambda: t.mul_(1.0))
+    copy = best(lambda: t[half:].copy_(t[:half]))
+    del t
+    torch.cuda.empty_cache()
+    return {"inplace_update_GBs": round(2 * 4 * n / inplace / 1e6, 1),
+            "device_copy_GBs": round(2 * 4 * half / copy / 1e6, 1),
+            "note": "torch x.mul_(1.0) over 6 GiB (reads + writes counted) and a 3 GiB -> 3 GiB copy"}
+
+
 def bench_calls(args, wl, q, grads, errs, codes, scales, x, m, v, werr, wcodes, code_bits, wcode_bytes):
     """The step as the three separate entry points; each group of launches is timed with HIP events
     on the stream the library launches on (torch's current stream)."""
@@ -154,10 +179,17 @@ def main():
     ap.add_argument("--path", choices=["fused", "calls"], default="fused",
                     help="fused: qadam_step_fused (the headline); calls: the same step as N x "
                          "qadam_worker_quantize + qadam_server_step + qadam_weight_quantize (variant S only)")
+    ap.add_argument("--rounding", type=int, choices=[0, 1], default=0,
+                    help="0: nearest (the paper's quantizers, the headline); 1: unbiased stochastic rounding "
+                         "driven by Philox4x32-10")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--alloc-cycles", type=int, default=5,
                     help="allocate and free the working set this many times before the real allocation "
                          "(0: measure on whatever placement a fresh process gets; see condition_allocator)")
+    ap.add_argument("--ceilings", action="store_true",
+                    help="also time plain torch streams over 6 GiB (an in-place update: half reads, half "
+                         "writes; a device copy) and add them to the JSON line as memory_system: what "
+                         "this box delivers to the simplest kernels, next to the 8 TB/s peak")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 4 GiB device copy (a kernel of known traffic, to scale "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -175,7 +207,8 @@ def main():
     wl = make_workload(args.config, shrink=args.shrink)
     P, N = wl.num_params, wl.num_workers
     weight_ef = 1
-    cfg = QAdamConfig(k_g=wl.k_g, k_x=wl.k_x, rounding=0, weight_ef=weight_ef, beta1=wl.beta1, eps=wl.eps)
+    cfg = QAdamConfig(k_g=wl.k_g, k_x=wl.k_x, rounding=args.rounding, weight_ef=weight_ef, beta1=wl.beta1,
+                      eps=wl.eps)
     q = QAdam(cfg, wl.seg_offsets, N)
     q.profile_enable(True)
     code_bits = q.grad_code_bytes() * 8.0 / P
@@ -204,6 +237,8 @@ def main():
         dst.copy_(src)                      # reads 4 GiB, writes 4 GiB
         torch.cuda.synchronize()
         del src, dst
+
+    memory_system = measure_ceilings(dev) if args.ceilings else None
 
     if args.path == "calls":
         if args.variant != "s":
@@ -269,9 +304,9 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "config %d: %s, %d logical workers, %d parameters in %d layers, "
-                               "k_g=%d (%d-bit codes), k_x=%d (%d-bit weights), weight_ef=1, nearest rounding, %s"
+                               "k_g=%d (%d-bit codes), k_x=%d (%d-bit weights), weight_ef=1, %s rounding, %s"
                                % (wl.config, wl.name, N, P, len(wl.sizes), wl.k_g, round(code_bits), wl.k_x,
-                                  8 * round(wcode_bytes),
+                                  8 * round(wcode_bytes), "stochastic (Philox)" if args.rounding else "nearest",
                                   "variant S (server moments)" if args.variant == "s" else
                                   "variant W (worker moments, Algorithms 2-3)"),
                    "worker_elements_per_s": N * P / (ms_per_step * 1e-3),
@@ -280,7 +315,7 @@ def main():
                    "status_word": status},
         "roofline": roofline,
     }
-    if not args.no_cpu_baseline and args.variant == "s":
+    if not args.no_cpu_baseline and args.variant == "s" and args.rounding == 0:
         # a bounded sample: the first layers after the token embedding, up to ~75 M parameters
         # (about 10 s of single-threaded oracle work); stops early after ~25 s
         sizes = wl.sizes
@@ -289,6 +324,8 @@ def main():
             if 0 < sizes[l] <= 20_000_000 and tot < 75_000_000:
                 pick.append(l); tot += sizes[l]
         out["cpu_baseline"] = cpu_baseline(wl, pick or [0], seconds_hint=25.0)
+    if memory_system:
+        out["memory_system"] = memory_system
     print(json.dumps(out), flush=True)
 
 

@@ -75,6 +75,10 @@ def load_library():
         raise ImportError(
             "%s is missing: build it with `python paper_2004_14180_amd/build.py` "
             "(hipcc, --offload-arch=gfx950). There is no fallback path." % _LIB_PATH)
+    # torch first: it ships its own HIP runtime under the same soname as the system's, and the
+    # process must end up with ONE runtime shared by torch (device memory, streams) and this library.
+    # Loaded the other way round, the library's HIP calls fail with "no ROCm-capable device".
+    import torch  # noqa: F401
     lib = C.CDLL(_LIB_PATH)
     vp, i32, i64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
     lib.qadam_init.argtypes = [C.POINTER(vp), C.POINTER(_Config), C.POINTER(i64), i32, i32]

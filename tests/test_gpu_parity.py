@@ -545,3 +545,54 @@ def test_layer_sumsq_and_assumption2_on_device():
                 assert a[l] < b[l], "Assumption 2 violated in layer %d of worker %d" % (l, i)
     assert q.get_status() == 0
     q.close()
+
+
+@pytest.mark.parametrize("variant", ["s", "w"])
+def test_closed_loop_on_device_follows_the_oracle(variant):
+    """The loop of Algorithms 2-3 run end to end on the device: workers take gradients of
+    f(x) = 1/2 ||x - x*||^2 at the dequantized broadcast Q_x(x_t) (qadam_weight_dequantize), the step
+    runs in the library, 300 iterations with alpha_t = alpha / sqrt(t).  The oracle runs the same loop
+    from its own state; the two trajectories stay bit-identical, and the iterate ends within a few
+    weight-grid steps of x* (Theorems 2-3, qualitatively)."""
+    n, N, T = 5000, 4, 300
+    gcfg, ocfg = configs(k_g=0, k_x=6, weight_ef=0)
+    rng = np.random.default_rng(17)
+    xstar = rng.uniform(-0.4, 0.4, n).astype(np.float32)
+    noise = (rng.standard_normal((T, N, n)) * 0.01).astype(np.float32)
+    seg = [0, 3000, n]
+    q = QAdam(gcfg, seg, N)
+    dev = "cuda"
+    z = lambda: torch.zeros(n, device=dev)
+    x, m, v, werr, xhat = z(), z(), z(), z(), z()
+    errs, grads = [z() for _ in range(N)], [z() for _ in range(N)]
+    mw, vw = [z() for _ in range(N)], [z() for _ in range(N)]
+    codes = [torch.zeros(q.grad_code_bytes() // 4, dtype=torch.int32, device=dev) for _ in range(N)]
+    scales = [torch.zeros(2, device=dev) for _ in range(N)]
+    wcodes = torch.zeros(n, dtype=torch.int8, device=dev)
+    xs_d, noise_d = torch.from_numpy(xstar).to(dev), torch.from_numpy(noise).to(dev)
+    # oracle state
+    hx, hw = np.zeros(n, np.float32), np.zeros(n, np.float32)
+    hm, hv = np.zeros(n, np.float32), np.zeros(n, np.float32)
+    he = [np.zeros(n, np.float32) for _ in range(N)]
+    hmw, hvw = [np.zeros(n, np.float32) for _ in range(N)], [np.zeros(n, np.float32) for _ in range(N)]
+    hxhat = np.zeros(n, np.float32)
+    for t in range(1, T + 1):
+        lr = float(np.float32(2e-2 / np.sqrt(t)))
+        for i in range(N):
+            grads[i].copy_((xhat - xs_d) + noise_d[t - 1, i])
+        hg = [((hxhat - xstar) + noise[t - 1, i]).astype(np.float32) for i in range(N)]
+        if variant == "s":
+            q.step_fused(t, lr, 0.999, grads, errs, codes, scales, x, m, v, werr, wcodes)
+            out = oracle.step_s(ocfg, seg, t, lr, 0.999, hg, he, hx, hm, hv, hw)
+        else:
+            q.step_fused_w(t, lr, 0.999, grads, mw, vw, errs, codes, scales, x, werr, wcodes)
+            out = oracle.step_w(ocfg, seg, t, lr, 0.999, hg, he, hmw, hvw, hx, hw)
+        q.weight_dequantize(wcodes, xhat)
+        hxhat = out["wcodes"].astype(np.float32) * np.float32(2.0 ** -7)
+        if t % 50 == 0 or t == T:
+            assert np.array_equal(xhat.cpu().numpy(), hxhat), t
+            assert np.array_equal(x.cpu().numpy().view(np.uint32), hx.view(np.uint32)), t
+    dist = np.abs(hxhat - xstar)
+    assert dist.max() < 6 * 2.0 ** -7
+    assert q.get_status() == 0
+    q.close()

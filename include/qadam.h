@@ -29,8 +29,12 @@
  *     passed the call.  Pointer arrays themselves and seg_offsets are HOST memory, read during
  *     the call only.
  *   - `stream` is a hipStream_t passed as void*.  Compute calls only enqueue work on it; they do
- *     not synchronise.  Calls on one handle must be issued in stream order (they share the
- *     handle's status word).
+ *     not synchronise.  Calls on one handle that touch the same worker, or the server state, must
+ *     be ordered by the caller (one stream, or events).  qadam_worker_quantize / qadam_worker_step_w
+ *     calls for DIFFERENT workers may run concurrently on different streams: the handle keeps
+ *     separate scratch rows per worker, and the status word is only ever OR-ed into.  The whole-step
+ *     calls and qadam_layer_sumsq use scratch of all workers, so they must not overlap anything else
+ *     on the same handle.
  *   - The parameter vector is flat, P = seg_offsets[L] elements, split into L layer segments
  *     [seg_offsets[l], seg_offsets[l+1]); empty segments are allowed.
  *   - `step` is the 1-based iteration t.

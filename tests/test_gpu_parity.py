@@ -596,3 +596,39 @@ def test_closed_loop_on_device_follows_the_oracle(variant):
     assert dist.max() < 6 * 2.0 ** -7
     assert q.get_status() == 0
     q.close()
+
+
+def test_workers_on_concurrent_streams():
+    """Worker calls of different workers enqueued on different streams (the handle keeps separate
+    scratch per worker), joined by events before the server call: same bits as the fused call."""
+    gcfg, _ = configs(k_g=2, k_x=6)
+    sizes = RAGGED + [1 << 20, 200000]
+    seg_off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    P, N = int(seg_off[-1]), 4
+    q = QAdam(gcfg, seg_off, N)
+    gen = torch.Generator().manual_seed(31)
+    x0 = torch.randn(P, generator=gen) * 0.02
+    a, b = DeviceState(q, x0), DeviceState(q, x0)
+    streams = [torch.cuda.Stream() for _ in range(N)]
+    main = torch.cuda.current_stream()
+    for t in range(1, 4):
+        for i in range(N):
+            g = torch.randn(P, generator=gen) * 0.01
+            a.grads[i].copy_(g); b.grads[i].copy_(g)
+        torch.cuda.synchronize()
+        for i in range(N):
+            q.worker_quantize(i, t, a.grads[i], a.errs[i], a.codes[i], a.scales[i], stream=streams[i])
+        for i in range(N):
+            main.wait_stream(streams[i])
+        q.server_step(t, 1e-3, 0.999, a.codes, a.scales, a.x, a.m, a.v)
+        q.weight_quantize(t, a.x, a.werr, a.wcodes)
+        torch.cuda.synchronize()
+        b.step_fused(t, 1e-3, 0.999)
+        torch.cuda.synchronize()
+        for name in ("x", "m", "v", "werr", "wcodes"):
+            assert torch.equal(getattr(a, name), getattr(b, name)), (t, name)
+        for i in range(N):
+            assert torch.equal(a.errs[i], b.errs[i]) and torch.equal(a.codes[i], b.codes[i]), (t, i)
+            assert torch.equal(a.scales[i], b.scales[i])
+    assert q.get_status() == 0
+    q.close()

@@ -37,18 +37,19 @@ def algorithmic_bytes_per_param(N, code_bits, wcode_bytes, weight_ef):
 
 
 def cpu_baseline(wl, sample_layers, seconds_hint=20.0):
-    """The oracle as it stands, one thread, on a bounded sample of the workload's layers."""
+    """The oracle as it stands, one thread, on a bounded sample of the workload's layers; then the same
+    calls once more spread over the host's cores (layers are independent), as a second figure."""
     import numpy as np
     import torch
+    from concurrent.futures import ThreadPoolExecutor
     from oracle import qadam_oracle as oracle
     offs = wl.seg_offsets
     N = wl.num_workers
     std = wl.layer_std()
     ocfg = oracle.OracleConfig(k_g=wl.k_g, k_x=wl.k_x, weight_ef=wl.weight_ef, beta1=wl.beta1, eps=wl.eps)
     g = torch.Generator().manual_seed(1234)
-    total, elapsed = 0, 0.0
-    used = []
-    for l in sample_layers:
+
+    def inputs(l):
         n = offs[l + 1] - offs[l]
         s = float(std[l])
         shared = torch.randn(n, generator=g) * s
@@ -58,16 +59,37 @@ def cpu_baseline(wl, sample_layers, seconds_hint=20.0):
         m = (torch.randn(n, generator=g) * (0.3 * s)).numpy()
         v = (torch.randn(n, generator=g) * s).square().numpy()
         w = ((torch.rand(n, generator=g) - 0.5) * 2.0 ** -(wl.k_x + 1)).numpy()
-        t0 = time.perf_counter()
+        return n, grads, errs, x, m, v, w
+
+    def step(l, data):
+        n, grads, errs, x, m, v, w = data
         oracle.step_s(ocfg, [0, n], 3, wl.lr, wl.beta2, grads, errs, x, m, v, w, index_base=offs[l], want_tie=False)
+
+    total, elapsed = 0, 0.0
+    used, kept = [], []
+    for l in sample_layers:
+        data = inputs(l)
+        t0 = time.perf_counter()
+        step(l, data)
         elapsed += time.perf_counter() - t0
-        total += n
+        total += data[0]
         used.append(l)
+        kept.append((l, data))
         if elapsed > seconds_hint:
             break
-    return {"value": total / elapsed, "unit": "params/s", "cores": 1, "kind": "oracle",
-            "sample": "one oracle step (variant S, %d workers) over layers %s of the workload = %d parameters, %.1f s"
-                      % (N, used, total, elapsed)}
+    out = {"value": total / elapsed, "unit": "params/s", "cores": 1, "kind": "oracle",
+           "sample": "one oracle step (variant S, %d workers) over layers %s of the workload = %d parameters, %.1f s"
+                     % (N, used, total, elapsed)}
+    # the same layers again (one more step from the state the first left), one layer per thread
+    threads = min(16, os.cpu_count() or 1, len(kept))
+    if threads > 1:
+        t0 = time.perf_counter()
+        with ThreadPoolExecutor(threads) as ex:
+            list(ex.map(lambda ld: step(*ld), kept))
+        dt = time.perf_counter() - t0
+        out["all_cores"] = {"value": total / dt, "unit": "params/s", "cores": threads,
+                            "note": "the same oracle calls, independent layers on %d threads, %.1f s" % (threads, dt)}
+    return out
 
 
 def condition_allocator(nbytes_list, cycles, device):

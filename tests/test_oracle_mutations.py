@@ -16,6 +16,8 @@ ORACLE_DIR = os.path.join(os.path.dirname(HERE), "oracle")
 # (name, text to find, replacement) -- each is one mistake a re-implementer could plausibly make
 MUTANTS = [
     ("residual_sign", "err[a + j] = p[j] - q[j];", "err[a + j] = p[j] + q[j];"),
+    ("error_buffer_accumulates", "err[a + j] = p[j] - q[j];", "err[a + j] = err[a + j] + (p[j] - q[j]);"),
+    ("error_feedback_dropped", "p[j] = grad[a + j] + err[a + j];     /* g + e */", "p[j] = grad[a + j];"),
     ("tie_goes_down", "if (a >= mid[c]) { mu = c; break; }", "if (a > mid[c]) { mu = c; break; }"),
     ("geometric_midpoint", "mid[c] = 0.5f * (lv[c - 1] + lv[c]);", "mid[c] = 0.70710678f * lv[c];"),
     ("level_off_by_one", "return mu == 0 ? 0.0f : ldexpf(1.0f, mu - 1 - k_g);", "return mu == 0 ? 0.0f : ldexpf(1.0f, mu - 2 - k_g);"),
@@ -82,6 +84,7 @@ def _battery():
         (ts.test_error_feedback_telescoping_variant_s, dict(k_g=2)), (ts.test_variant_w_telescoping, {}),
         (ts.test_variant_s_server_mean_and_order, {}), (ts.test_fused_step_equals_three_calls, {}),
         (ts.test_window_equals_layer, {}), (ts.test_step_window_equals_step, {}),
+        (ts.test_error_buffer_obeys_the_geometric_bound, dict(k_g=2)),
     ]
     return calls
 

@@ -144,6 +144,34 @@ def test_error_feedback_telescoping_variant_s(oracle, k_g):
         assert np.max(np.abs(errs[i])) < 0.2      # a few gradient magnitudes, not growing with T
 
 
+@pytest.mark.parametrize("k_g", [0, 2])
+def test_error_buffer_obeys_the_geometric_bound(oracle, k_g):
+    """Lemma on the error term (proof of Theorem 1): with contraction factor c = 1 - delta_g of the
+    quantizer (Assumption 2), ||e_{t+1}|| <= sum_{i<=t} c^(t-i+1) ||Delta_i||.  Here Delta_i is what
+    the worker feeds in at step i (its gradient in variant S) and c is the largest per-step ratio
+    ||p - Q_g(p)|| / ||p|| actually observed (< 1); norms per layer in fp64.  An error buffer that
+    accumulated instead of being replaced, or a residual of the wrong sign, breaks the bound."""
+    n, T = 4096, 60
+    rng = np.random.default_rng(40 + k_g)
+    cfg = OracleConfig(k_g=k_g, k_x=6)
+    err = np.zeros(n, np.float32)
+    d_norm, e_norm, ratios = [], [], []
+    for t in range(1, T + 1):
+        g = (rng.standard_normal(n) * (1e-2 * (1 + (t % 7)))).astype(np.float32)   # uneven step sizes
+        p = (g + err).astype(np.float64)
+        oracle.worker_quantize(cfg, [0, n], 0, t, g, err)
+        d_norm.append(np.linalg.norm(g.astype(np.float64)))
+        e_norm.append(np.linalg.norm(err.astype(np.float64)))
+        ratios.append(e_norm[-1] / np.linalg.norm(p))
+    c = max(ratios)
+    assert c < 1.0                                   # Assumption 2 held at every step
+    for t in range(T):
+        bound = sum(c ** (t - i + 1) * d_norm[i] for i in range(t + 1))
+        assert e_norm[t] <= bound * (1 + 1e-9), t
+    # the bound's limit: the buffer never exceeds c/(1-c) times the largest input
+    assert max(e_norm) <= c / (1 - c) * max(d_norm)
+
+
 def test_variant_w_telescoping(oracle):
     """Notation 3: x~_t = x_t - mean_i e_t^(i) follows the un-quantized recursion
     x~_{t+1} = x~_t + mean_i Delta_t^(i), Delta = -alpha m / sqrt(v + eps) with the workers' own

@@ -85,6 +85,8 @@ def _battery():
         (ts.test_variant_s_server_mean_and_order, {}), (ts.test_fused_step_equals_three_calls, {}),
         (ts.test_window_equals_layer, {}), (ts.test_step_window_equals_step, {}),
         (ts.test_error_buffer_obeys_the_geometric_bound, dict(k_g=2)),
+        (ts.test_whole_step_against_the_definitions_in_fp64, dict(variant="s")),
+        (ts.test_whole_step_against_the_definitions_in_fp64, dict(variant="w")),
     ]
     return calls
 

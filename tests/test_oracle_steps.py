@@ -370,3 +370,91 @@ def test_closed_loop_quadratic_reaches_a_neighbourhood(oracle, variant):
     dist = np.abs(xhat - xstar)
     assert np.linalg.norm(xhat - xstar) < 0.05 * d0
     assert dist.max() < 4 * 2.0 ** -7                                    # a few weight-grid steps
+
+
+def _real_qg(p, k_g):
+    """Q_g of Sec. 5.1 from its definition, in fp64: ||p||_inf times the nearest point of
+    G = {0, +-2^-k_g, ..., +-1} to p / ||p||_inf.  Returns (q, distance of |p|/s to the nearest midpoint)."""
+    s = np.max(np.abs(p))
+    if s == 0:
+        return np.zeros_like(p), np.ones_like(p)
+    grid = np.array([0.0] + [2.0 ** (c - 1 - k_g) for c in range(1, k_g + 2)])
+    a = np.abs(p) / s
+    idx = np.argmin(np.abs(a[:, None] - grid[None, :]), axis=1)
+    mids = 0.5 * (grid[:-1] + grid[1:])
+    margin = np.min(np.abs(a[:, None] - mids[None, :]), axis=1)
+    return np.sign(p) * s * grid[idx], margin
+
+
+@pytest.mark.parametrize("variant", ["s", "w"])
+def test_whole_step_against_the_definitions_in_fp64(oracle, variant):
+    """One step of each variant re-evaluated from the paper's formulas over the reals (numpy fp64,
+    arg-min by enumeration of the grids, no shared code): the oracle's binary32 result agrees to
+    rounding, and its integer codes agree wherever the value is not within 1e-5 of a midpoint."""
+    n, N, k_g, k_x = 6000, 3, 2, 6
+    segs = [0, 2500, 2600, n]
+    rng = np.random.default_rng(77)
+    cfg = OracleConfig(k_g=k_g, k_x=k_x, weight_ef=1, beta1=0.9, eps=1e-8)
+    beta, theta, eps, lr = (np.float64(np.float32(c)) for c in (0.9, 0.999, 1e-8, 1e-3))
+    grads = [(rng.standard_normal(n) * 1e-2).astype(np.float32) for _ in range(N)]
+    errs = [(rng.standard_normal(n) * 2e-3).astype(np.float32) for _ in range(N)]
+    x = (rng.standard_normal(n) * 0.02).astype(np.float32)
+    werr = ((rng.random(n) - 0.5) * 2.0 ** -(k_x + 1)).astype(np.float32)
+    m = (rng.standard_normal(n) * 3e-3).astype(np.float32)
+    v = ((rng.standard_normal(n) * 1e-2) ** 2).astype(np.float32)
+    mw = [(rng.standard_normal(n) * 3e-3).astype(np.float32) for _ in range(N)]
+    vw = [((rng.standard_normal(n) * 1e-2) ** 2).astype(np.float32) for _ in range(N)]
+    # ---- the definitions, fp64
+    acc = np.zeros(n)
+    pmax = 0.0
+    e_want, safe = [], np.ones(n, bool)
+    m_want = v_want = None
+    mw_want, vw_want = [], []
+    for i in range(N):
+        if variant == "s":
+            value = grads[i].astype(np.float64)
+        else:                                   # Algorithm 3: local moments, then the Adam update
+            g = grads[i].astype(np.float64)
+            vv = theta * vw[i] + (1 - theta) * g * g
+            mm = beta * mw[i] + (1 - beta) * g
+            mw_want.append(mm); vw_want.append(vv)
+            value = lr * mm / np.sqrt(vv + eps)
+        p = value + errs[i]
+        q = np.zeros(n)
+        for l in range(len(segs) - 1):
+            a, b = segs[l], segs[l + 1]
+            q[a:b], margin = _real_qg(p[a:b], k_g)
+            safe[a:b] &= margin > 1e-5
+        e_want.append(p - q)
+        pmax = max(pmax, float(np.max(np.abs(p))))
+        acc += q
+    mean = acc / N
+    if variant == "s":
+        v_want = theta * v + (1 - theta) * mean * mean
+        m_want = beta * m + (1 - beta) * mean
+        x_want = x - lr * m_want / np.sqrt(v_want + eps)
+    else:
+        x_want = x - mean
+    y = x_want + werr
+    u = y * 2.0 ** (k_x + 1)
+    safe_x = np.abs(np.abs(u - np.floor(u)) - 0.5) > 1e-3
+    j_want = np.clip(np.sign(u) * np.floor(np.abs(u) + 0.5), -2.0 ** k_x, 2.0 ** k_x)
+    werr_want = y - j_want * 2.0 ** -(k_x + 1)
+    # ---- the oracle, binary32
+    if variant == "s":
+        out = oracle.step_s(cfg, segs, 5, float(lr), float(theta), grads, errs, x, m, v, werr)
+    else:
+        out = oracle.step_w(cfg, segs, 5, float(lr), float(theta), grads, errs, mw, vw, x, werr)
+    assert safe.mean() > 0.99 and safe_x.mean() > 0.99
+    # binary32 rounds the scale s = ||p||_inf, and with it every q = s * level, by up to half an ulp of s
+    tol = dict(rtol=3e-6, atol=2.0 ** -22 * pmax)
+    for i in range(N):
+        assert np.allclose(errs[i][safe], e_want[i][safe], **tol), i
+        if variant == "w":
+            assert np.allclose(mw[i], mw_want[i], **tol) and np.allclose(vw[i], vw_want[i], rtol=3e-6, atol=1e-12)
+    if variant == "s":
+        assert np.allclose(m[safe], m_want[safe], **tol) and np.allclose(v[safe], v_want[safe], rtol=3e-6, atol=1e-12)
+    assert np.allclose(x[safe], x_want[safe], rtol=3e-6, atol=max(1e-8, 2.0 ** -22 * pmax))
+    ok = safe & safe_x
+    assert np.array_equal(out["wcodes"][ok].astype(np.float64), j_want[ok])
+    assert np.allclose(werr[ok], werr_want[ok], rtol=0, atol=1e-7)

@@ -376,9 +376,10 @@ def test_small_tile_sizes(monkeypatch):
         assert rep.ok() and st == 0, tile
 
 
-@pytest.mark.parametrize("N,rounding", [(4, 0), (3, 0), (2, 1)])
+@pytest.mark.parametrize("N,rounding", [(4, 0), (3, 0), (2, 1), (1, 0), (8, 0)])
 def test_variant_w_fused_step(N, rounding):
-    """qadam_step_fused_w against the oracle's Algorithms 2-3 and against the separate calls."""
+    """qadam_step_fused_w against the oracle's Algorithms 2-3 and against the separate calls
+    (N = 1 is the single-machine Algorithm 1)."""
     gcfg, ocfg = configs(k_g=2, k_x=6, rounding=rounding, seed=5, eps=1e-6)
     sizes = RAGGED + [30000]
     seg_off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)

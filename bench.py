@@ -30,9 +30,10 @@ MEASURED_TRAFFIC_BYTES = {5: 174.33e9}
 def algorithmic_bytes_per_param(N, code_bits, wcode_bytes, weight_ef):
     """Bytes the method itself must move per parameter in the fused main pass, one trip per buffer:
     per worker read g and e, write e and the packed code; server read and write m, v, x, read and
-    write (or only write) e^x, write the weight code."""
-    worker = 12.0 + code_bits / 8.0
-    server = 24.0 + (8.0 if weight_ef else 4.0) + wcode_bytes
+    write (or only write) e^x, write the weight code.  code_bits == 0: Q_g is the identity (the
+    workers' gradients are read, nothing else); wcode_bytes == 0: Q_x is the identity."""
+    worker = 12.0 + code_bits / 8.0 if code_bits else 4.0
+    server = 24.0 + ((8.0 if weight_ef else 4.0) + wcode_bytes if wcode_bytes else 0.0)
     return N * worker + server
 
 
@@ -204,6 +205,11 @@ def main():
     ap.add_argument("--rounding", type=int, choices=[0, 1], default=0,
                     help="0: nearest (the paper's quantizers, the headline); 1: unbiased stochastic rounding "
                          "driven by Philox4x32-10")
+    ap.add_argument("--k-g", type=int, default=None,
+                    help="override the workload's gradient grid (0: 2-bit codes, 1-2: 3-bit, 3-6: 4-bit, "
+                         "-1: no gradient quantization)")
+    ap.add_argument("--k-x", type=int, default=None,
+                    help="override the workload's weight grid (0-6: int8, 7-14: int16, -1: no weight quantization)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--alloc-cycles", type=int, default=5,
                     help="allocate and free the working set this many times before the real allocation "
@@ -227,6 +233,10 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     wl = make_workload(args.config, shrink=args.shrink)
+    if args.k_g is not None:
+        wl.k_g = args.k_g
+    if args.k_x is not None:
+        wl.k_x = args.k_x
     P, N = wl.num_params, wl.num_workers
     weight_ef = 1
     cfg = QAdamConfig(k_g=wl.k_g, k_x=wl.k_x, rounding=args.rounding, weight_ef=weight_ef, beta1=wl.beta1,
@@ -249,7 +259,7 @@ def main():
     if args.variant == "w":
         mw = [z() for _ in range(N)]
         vw = [z() for _ in range(N)]
-    codes = [torch.empty(q.grad_code_bytes() // 4, dtype=torch.int32, device=dev) for _ in range(N)]
+    codes = [torch.empty(max(q.grad_code_bytes() // 4, 4), dtype=torch.int32, device=dev) for _ in range(N)]
     scales = [torch.empty(q.num_segments, dtype=torch.float32, device=dev) for _ in range(N)]
     wcodes = torch.empty(P, dtype=torch.int8 if wl.k_x <= 6 else torch.int16, device=dev)
 
@@ -304,16 +314,18 @@ def main():
                                     "achieved": round(a_second * P / (main_avg * 1e-3) / 1e9, 1)},
                     "whole_step_GBs": round((a_first + a_second) * P / (ms_per_step * 1e-3) / 1e9, 1)}
     a_main = algorithmic_bytes_per_param(N, code_bits, wcode_bytes, weight_ef)
+    a_scale = 8.0 * N if code_bits else 0.0
     achieved = a_main * P / (main_avg * 1e-3) / 1e9
     roofline_s = {"bound": "hbm", "kernel": "k_fused (main pass of qadam_step_fused)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get(args.config) if args.shrink == 1 else None,
+                "traffic": MEASURED_TRAFFIC_BYTES.get(args.config)
+                if args.shrink == 1 and args.k_g is None and args.k_x is None and args.rounding == 0 else None,
                 "algorithmic_bytes_per_param": a_main,
                 "avg_launch_ms": round(main_avg, 4),
-                "scale_pass": {"algorithmic_bytes_per_param": 8.0 * N, "avg_launch_ms": round(scale_avg, 4),
-                               "achieved": round(8.0 * N * P / (scale_avg * 1e-3) / 1e9, 1)},
-                "whole_step_GBs": round((a_main + 8.0 * N) * P / (ms_per_step * 1e-3) / 1e9, 1)}
+                "scale_pass": {"algorithmic_bytes_per_param": a_scale, "avg_launch_ms": round(scale_avg, 4),
+                               "achieved": round(a_scale * P / (max(scale_avg, 1e-6) * 1e-3) / 1e9, 1)},
+                "whole_step_GBs": round((a_main + a_scale) * P / (ms_per_step * 1e-3) / 1e9, 1)}
     if args.variant == "s":
         roofline = roofline_s
 
@@ -326,7 +338,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "config %d: %s, %d logical workers, %d parameters in %d layers, "
-                               "k_g=%d (%d-bit codes), k_x=%d (%d-bit weights), weight_ef=1, %s rounding, %s"
+                               "k_g=%d (%d-bit codes), k_x=%d (%d-bit weights; 0 bits = quantizer off), weight_ef=1, %s rounding, %s"
                                % (wl.config, wl.name, N, P, len(wl.sizes), wl.k_g, round(code_bits), wl.k_x,
                                   8 * round(wcode_bytes), "stochastic (Philox)" if args.rounding else "nearest",
                                   "variant S (server moments)" if args.variant == "s" else
@@ -337,7 +349,7 @@ def main():
                    "status_word": status},
         "roofline": roofline,
     }
-    if not args.no_cpu_baseline and args.variant == "s" and args.rounding == 0:
+    if not args.no_cpu_baseline and args.variant == "s" and args.rounding == 0 and wl.k_g >= 0 and wl.k_x >= 0:
         # a bounded sample: the first layers after the token embedding, up to ~75 M parameters
         # (about 10 s of single-threaded oracle work); stops early after ~25 s
         sizes = wl.sizes

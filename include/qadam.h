@@ -72,6 +72,19 @@ extern "C" {
 
 #define QADAM_MAX_WORKERS 32
 
+/* k_g or k_x = QADAM_IDENTITY: that quantizer is the identity.  These are the settings of the paper's
+ * Theorem 1 (Q_x = id: gradient quantization with error feedback, full-precision weights) and Theorem 2
+ * (Q_g = id: full-precision messages, quantized weights), and of the corresponding rows of Tables 1-2;
+ * both = plain (distributed) generic Adam.  Only the whole-step calls run in these modes:
+ *   Q_g = id, qadam_step_fused:   the message of worker i is g_i itself; errs, codes and scales are not
+ *                                 used (the arrays may be NULL); qadam_grad_code_bytes is 0;
+ *   Q_g = id, qadam_step_fused_w: the message is alpha_t m_i / sqrt(v_i + eps) + e_i and e_i <- 0 (the
+ *                                 error buffers are still needed as working space); codes, scales unused;
+ *   Q_x = id:                     no weight codes and no weight residual are produced (werr_dev and
+ *                                 wcodes_dev may be NULL); qadam_weight_code_bytes is 0.
+ * The single-purpose calls of a quantizer that is switched off return QADAM_EINVAL. */
+#define QADAM_IDENTITY (-1)
+
 /* status word bits */
 #define QADAM_STATUS_NONFINITE_SCALE 1u   /* some ||g+e||_inf was NaN or Inf */
 
@@ -79,8 +92,9 @@ typedef struct qadam_ctx* qadam_handle_t;
 
 typedef struct {
     uint32_t struct_size;   /* = sizeof(qadam_config_t) */
-    int32_t  k_g;           /* Q_g grid exponent count, 0..6 (0 = ternary)                     Sec. 5.1 */
-    int32_t  k_x;           /* Q_x grid: multiples of 2^-(k_x+1) on [-1/2, 1/2], 0..14          Sec. 5.1 */
+    int32_t  k_g;           /* Q_g grid exponent count, 0..6 (0 = ternary), or QADAM_IDENTITY    Sec. 5.1 */
+    int32_t  k_x;           /* Q_x grid: multiples of 2^-(k_x+1) on [-1/2, 1/2], 0..14,
+                               or QADAM_IDENTITY                                                 Sec. 5.1 */
     int32_t  rounding;      /* 0 = nearest, a midpoint goes to the larger magnitude (the paper's arg-min);
                                1 = unbiased stochastic rounding driven by Philox4x32-10 keyed on
                                (seed; element index, step, worker, stream) */

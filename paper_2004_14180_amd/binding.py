@@ -16,6 +16,7 @@ _LIB_PATH = os.path.join(_HERE, "libqadam_hip.so")
 
 QADAM_OK, QADAM_EINVAL, QADAM_EALIGN, QADAM_ERANGE, QADAM_EHIP = 0, -1, -2, -3, -4
 QADAM_MAX_WORKERS = 32
+QADAM_IDENTITY = -1          # k_g or k_x: that quantizer is the identity
 QADAM_STATUS_NONFINITE_SCALE = 1
 
 EXPORTS = [
@@ -118,7 +119,9 @@ def _ptr(t) -> Optional[int]:
     return t.data_ptr()
 
 
-def _ptr_array(ts: Sequence):
+def _ptr_array(ts: Optional[Sequence]):
+    if ts is None:
+        return None
     arr = (C.c_void_p * len(ts))()
     for i, t in enumerate(ts):
         arr[i] = _ptr(t)

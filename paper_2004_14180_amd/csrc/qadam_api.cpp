@@ -137,22 +137,31 @@ int check_ptr(const void* p, const char* name, bool required = true)
         if (rc_ != QADAM_OK) return rc_;  \
     } while (0)
 
+bool identity_g(const qadam_ctx* h) { return h->cfg.k_g == QADAM_IDENTITY; }
+bool identity_x(const qadam_ctx* h) { return h->cfg.k_x == QADAM_IDENTITY; }
+
 int fill_worker_tables(const qadam_ctx* h, WorkerPtrs& W, const float* const* grads, float* const* errs,
-                       void* const* codes, float* const* scales, bool need_grad_err)
+                       void* const* codes, float* const* scales, bool need_grad, bool need_err, bool need_codes)
 {
     std::memset(&W, 0, sizeof W);
-    if (!codes || !scales || (need_grad_err && (!grads || !errs))) return fail(QADAM_EINVAL, "null pointer array");
+    if ((need_codes && (!codes || !scales)) || (need_grad && !grads) || (need_err && !errs))
+        return fail(QADAM_EINVAL, "null pointer array");
     const bool empty = h->num_params == 0;
     for (int i = 0; i < h->num_workers; ++i) {
-        if (need_grad_err) {
+        if (need_grad) {
             QADAM_CHECK(check_ptr(grads[i], "grads[i]", !empty));
-            QADAM_CHECK(check_ptr(errs[i], "errs[i]", !empty));
-            W.grad[i] = grads[i]; W.err[i] = errs[i];
+            W.grad[i] = grads[i];
         }
-        QADAM_CHECK(check_ptr(codes[i], "codes[i]", !empty));
-        QADAM_CHECK(check_ptr(scales[i], "scales[i]", h->num_segments > 0));
-        W.codes[i] = static_cast<uint32_t*>(codes[i]);
-        W.scales[i] = scales[i];
+        if (need_err) {
+            QADAM_CHECK(check_ptr(errs[i], "errs[i]", !empty));
+            W.err[i] = errs[i];
+        }
+        if (need_codes) {
+            QADAM_CHECK(check_ptr(codes[i], "codes[i]", !empty));
+            QADAM_CHECK(check_ptr(scales[i], "scales[i]", h->num_segments > 0));
+            W.codes[i] = static_cast<uint32_t*>(codes[i]);
+            W.scales[i] = scales[i];
+        }
     }
     return QADAM_OK;
 }
@@ -169,8 +178,10 @@ int qadam_init(qadam_handle_t* out, const qadam_config_t* cfg, const int64_t* se
     if (!out || !cfg || !seg_offsets) return fail(QADAM_EINVAL, "null argument");
     *out = nullptr;
     if (cfg->struct_size != sizeof(qadam_config_t)) return fail(QADAM_EINVAL, "config struct_size mismatch");
-    if (cfg->k_g < 0 || cfg->k_g > 6) return fail(QADAM_EINVAL, "k_g outside 0..6");
-    if (cfg->k_x < 0 || cfg->k_x > 14) return fail(QADAM_EINVAL, "k_x outside 0..14");
+    if (cfg->k_g != QADAM_IDENTITY && (cfg->k_g < 0 || cfg->k_g > 6))
+        return fail(QADAM_EINVAL, "k_g outside 0..6 (or QADAM_IDENTITY)");
+    if (cfg->k_x != QADAM_IDENTITY && (cfg->k_x < 0 || cfg->k_x > 14))
+        return fail(QADAM_EINVAL, "k_x outside 0..14 (or QADAM_IDENTITY)");
     if ((cfg->rounding | 1) != 1 || (cfg->weight_ef | 1) != 1 || (cfg->adam_flavor | 1) != 1)
         return fail(QADAM_EINVAL, "rounding, weight_ef and adam_flavor are 0 or 1");
     if (!(cfg->beta1 >= 0.0f && cfg->beta1 < 1.0f)) return fail(QADAM_EINVAL, "beta1 outside [0,1)");
@@ -191,9 +202,9 @@ int qadam_init(qadam_handle_t* out, const qadam_config_t* cfg, const int64_t* se
     h->num_workers = num_workers;
     h->num_segments = num_segments;
     h->num_params = P;
-    h->mu_bits = mu_bits_for(cfg->k_g);
-    h->code_bits = 1 + h->mu_bits;
-    h->wcode_bytes = cfg->k_x <= 6 ? 1 : 2;
+    h->mu_bits = cfg->k_g == QADAM_IDENTITY ? 0 : mu_bits_for(cfg->k_g);
+    h->code_bits = cfg->k_g == QADAM_IDENTITY ? 0 : 1 + h->mu_bits;       /* 0: no codes are stored */
+    h->wcode_bytes = cfg->k_x == QADAM_IDENTITY ? 0 : (cfg->k_x <= 6 ? 1 : 2);
     h->tile_elems = tile_elems_from_env();
 
     // one workgroup per tile: a launch needs tiles * threads per workgroup below 2^32
@@ -287,6 +298,7 @@ int qadam_worker_quantize(qadam_handle_t h, int32_t worker, int64_t step, const 
                           float* err_dev, void* codes_dev, float* scales_dev, void* stream)
 {
     QADAM_CHECK(check_handle(h));
+    if (identity_g(h)) return fail(QADAM_EINVAL, "the handle has no gradient quantizer (k_g = QADAM_IDENTITY)");
     if (worker < 0 || worker >= h->num_workers) return fail(QADAM_EINVAL, "worker out of range");
     if (step < 1) return fail(QADAM_EINVAL, "step < 1");
     const bool empty = h->num_params == 0;
@@ -310,11 +322,12 @@ int qadam_server_step(qadam_handle_t h, int64_t step, float lr, float beta2, con
                       const float* const* scales, float* x_dev, float* m_dev, float* v_dev, void* stream)
 {
     QADAM_CHECK(check_handle(h));
+    if (identity_g(h)) return fail(QADAM_EINVAL, "the handle has no gradient quantizer (k_g = QADAM_IDENTITY)");
     if (step < 1) return fail(QADAM_EINVAL, "step < 1");
     const bool empty = h->num_params == 0;
     WorkerPtrs W;
     QADAM_CHECK(fill_worker_tables(h, W, nullptr, nullptr, const_cast<void* const*>(codes),
-                                   const_cast<float* const*>(scales), false));
+                                   const_cast<float* const*>(scales), false, false, true));
     QADAM_CHECK(check_ptr(x_dev, "x_dev", !empty));
     QADAM_CHECK(check_ptr(m_dev, "m_dev", !empty));
     QADAM_CHECK(check_ptr(v_dev, "v_dev", !empty));
@@ -329,6 +342,7 @@ int qadam_weight_quantize(qadam_handle_t h, int64_t step, const float* x_dev, fl
                           void* wcodes_dev, void* stream)
 {
     QADAM_CHECK(check_handle(h));
+    if (identity_x(h)) return fail(QADAM_EINVAL, "the handle has no weight quantizer (k_x = QADAM_IDENTITY)");
     if (step < 1) return fail(QADAM_EINVAL, "step < 1");
     const bool empty = h->num_params == 0;
     QADAM_CHECK(check_ptr(x_dev, "x_dev", !empty));
@@ -342,6 +356,7 @@ int qadam_weight_quantize(qadam_handle_t h, int64_t step, const float* x_dev, fl
 int qadam_weight_dequantize(qadam_handle_t h, const void* wcodes_dev, float* xhat_dev, void* stream)
 {
     QADAM_CHECK(check_handle(h));
+    if (identity_x(h)) return fail(QADAM_EINVAL, "the handle has no weight quantizer (k_x = QADAM_IDENTITY)");
     const bool empty = h->num_params == 0;
     QADAM_CHECK(check_ptr(wcodes_dev, "wcodes_dev", !empty));
     QADAM_CHECK(check_ptr(xhat_dev, "xhat_dev", !empty));
@@ -353,6 +368,7 @@ int qadam_weight_dequantize(qadam_handle_t h, const void* wcodes_dev, float* xha
 int qadam_weight_dequantize_f16(qadam_handle_t h, const void* wcodes_dev, void* xhat_dev, void* stream)
 {
     QADAM_CHECK(check_handle(h));
+    if (identity_x(h)) return fail(QADAM_EINVAL, "the handle has no weight quantizer (k_x = QADAM_IDENTITY)");
     const bool empty = h->num_params == 0;
     QADAM_CHECK(check_ptr(wcodes_dev, "wcodes_dev", !empty));
     QADAM_CHECK(check_ptr(xhat_dev, "xhat_dev", !empty));
@@ -369,21 +385,26 @@ int qadam_step_fused(qadam_handle_t h, int64_t step, float lr, float beta2, cons
     if (step < 1) return fail(QADAM_EINVAL, "step < 1");
     const bool empty = h->num_params == 0;
     WorkerPtrs W;
-    QADAM_CHECK(fill_worker_tables(h, W, grads, errs, codes, scales, true));
+    const bool idg = identity_g(h), idx = identity_x(h);
+    QADAM_CHECK(fill_worker_tables(h, W, grads, errs, codes, scales, true, !idg, !idg));
     QADAM_CHECK(check_ptr(x_dev, "x_dev", !empty));
     QADAM_CHECK(check_ptr(m_dev, "m_dev", !empty));
     QADAM_CHECK(check_ptr(v_dev, "v_dev", !empty));
-    QADAM_CHECK(check_ptr(werr_dev, "werr_dev", !empty && h->cfg.weight_ef == 1));
-    QADAM_CHECK(check_ptr(wcodes_dev, "wcodes_dev", !empty));
+    QADAM_CHECK(check_ptr(werr_dev, "werr_dev", !empty && !idx && h->cfg.weight_ef == 1));
+    QADAM_CHECK(check_ptr(wcodes_dev, "wcodes_dev", !empty && !idx));
     ServerPtrs sp;
-    sp.x = x_dev; sp.m = m_dev; sp.v = v_dev; sp.werr = werr_dev; sp.wcodes = wcodes_dev;
+    sp.x = x_dev; sp.m = m_dev; sp.v = v_dev;
+    sp.werr = idx ? nullptr : werr_dev; sp.wcodes = idx ? nullptr : wcodes_dev;
     const StepScalars S = make_scalars(h, step, lr, beta2);
     const Launch L = make_launch(h, stream);
     if (h->profile) QADAM_HIP(hipEventRecord(h->ev[0], L.stream));
-    QADAM_HIP(launch_amax(L, S, W, 0, h->num_workers));
-    QADAM_HIP(launch_reduce_scales(L, W, 0, h->num_workers));
+    if (!idg) {
+        QADAM_HIP(launch_amax(L, S, W, 0, h->num_workers));
+        QADAM_HIP(launch_reduce_scales(L, W, 0, h->num_workers));
+    }
     if (h->profile) QADAM_HIP(hipEventRecord(h->ev[1], L.stream));
-    QADAM_HIP(launch_fused(L, S, W, sp));
+    if (idg) QADAM_HIP(launch_plain_messages(L, S, W, sp, false));
+    else QADAM_HIP(launch_fused(L, S, W, sp));
     if (h->profile) {
         QADAM_HIP(hipEventRecord(h->ev[2], L.stream));
         h->profile_valid = true;
@@ -396,6 +417,7 @@ int qadam_worker_step_w(qadam_handle_t h, int32_t worker, int64_t step, float lr
                         void* codes_dev, float* scales_dev, void* stream)
 {
     QADAM_CHECK(check_handle(h));
+    if (identity_g(h)) return fail(QADAM_EINVAL, "the handle has no gradient quantizer (k_g = QADAM_IDENTITY)");
     if (worker < 0 || worker >= h->num_workers) return fail(QADAM_EINVAL, "worker out of range");
     if (step < 1) return fail(QADAM_EINVAL, "step < 1");
     const bool empty = h->num_params == 0;
@@ -429,26 +451,29 @@ int qadam_step_fused_w(qadam_handle_t h, int64_t step, float lr, float beta2, co
     if (!mw || !vw) return fail(QADAM_EINVAL, "null pointer array");
     const bool empty = h->num_params == 0;
     WorkerPtrs W;
-    QADAM_CHECK(fill_worker_tables(h, W, grads, errs, codes, scales, true));
+    const bool idg = identity_g(h), idx = identity_x(h);
+    QADAM_CHECK(fill_worker_tables(h, W, grads, errs, codes, scales, true, true, !idg));
     for (int i = 0; i < h->num_workers; ++i) {
         QADAM_CHECK(check_ptr(mw[i], "mw[i]", !empty));
         QADAM_CHECK(check_ptr(vw[i], "vw[i]", !empty));
         W.mw[i] = mw[i]; W.vw[i] = vw[i];
     }
     QADAM_CHECK(check_ptr(x_dev, "x_dev", !empty));
-    QADAM_CHECK(check_ptr(werr_dev, "werr_dev", !empty && h->cfg.weight_ef == 1));
-    QADAM_CHECK(check_ptr(wcodes_dev, "wcodes_dev", !empty));
+    QADAM_CHECK(check_ptr(werr_dev, "werr_dev", !empty && !idx && h->cfg.weight_ef == 1));
+    QADAM_CHECK(check_ptr(wcodes_dev, "wcodes_dev", !empty && !idx));
     ServerPtrs sp;
-    sp.x = x_dev; sp.m = nullptr; sp.v = nullptr; sp.werr = werr_dev; sp.wcodes = wcodes_dev;
+    sp.x = x_dev; sp.m = nullptr; sp.v = nullptr;
+    sp.werr = idx ? nullptr : werr_dev; sp.wcodes = idx ? nullptr : wcodes_dev;
     const StepScalars S = make_scalars(h, step, lr, beta2);
     const Launch L = make_launch(h, stream);
     if (h->profile) QADAM_HIP(hipEventRecord(h->ev[0], L.stream));
     // pass 1 (all workers): local moments, p parked in the error buffers, tile maxima; then scales
     QADAM_HIP(launch_worker_moments_w(L, S, W, 0, h->num_workers));
-    QADAM_HIP(launch_reduce_scales(L, W, 0, h->num_workers));
+    if (!idg) QADAM_HIP(launch_reduce_scales(L, W, 0, h->num_workers));
     if (h->profile) QADAM_HIP(hipEventRecord(h->ev[1], L.stream));
     // pass 2: quantize every worker's parked p, subtract the mean message, Q_x
-    QADAM_HIP(launch_fused_w(L, S, W, sp));
+    if (idg) QADAM_HIP(launch_plain_messages(L, S, W, sp, true));
+    else QADAM_HIP(launch_fused_w(L, S, W, sp));
     if (h->profile) {
         QADAM_HIP(hipEventRecord(h->ev[2], L.stream));
         h->profile_valid = true;
@@ -460,10 +485,11 @@ int qadam_server_apply_w(qadam_handle_t h, int64_t step, const void* const* code
                          const float* const* scales, float* x_dev, void* stream)
 {
     QADAM_CHECK(check_handle(h));
+    if (identity_g(h)) return fail(QADAM_EINVAL, "the handle has no gradient quantizer (k_g = QADAM_IDENTITY)");
     if (step < 1) return fail(QADAM_EINVAL, "step < 1");
     WorkerPtrs W;
     QADAM_CHECK(fill_worker_tables(h, W, nullptr, nullptr, const_cast<void* const*>(codes),
-                                   const_cast<float* const*>(scales), false));
+                                   const_cast<float* const*>(scales), false, false, true));
     QADAM_CHECK(check_ptr(x_dev, "x_dev", h->num_params != 0));
     const StepScalars S = make_scalars(h, step, 0.0f, 0.0f);
     QADAM_HIP(launch_server_apply_w(make_launch(h, stream), S, W, x_dev));

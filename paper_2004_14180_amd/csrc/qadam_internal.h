@@ -83,6 +83,10 @@ hipError_t launch_server_step(const Launch& L, const StepScalars& S, const Worke
 hipError_t launch_weight_quantize(const Launch& L, const StepScalars& S, const float* x, float* werr, void* wcodes);
 hipError_t launch_weight_dequantize(const Launch& L, const StepScalars& S, const void* wcodes, void* xhat, bool half);
 hipError_t launch_fused(const Launch& L, const StepScalars& S, const WorkerPtrs& W, const ServerPtrs& sp);
+// Q_g = identity: the messages are fp32 values (variant S: the gradients; variant W: the parked
+// update + error, whose buffers are then cleared)
+hipError_t launch_plain_messages(const Launch& L, const StepScalars& S, const WorkerPtrs& W, const ServerPtrs& sp,
+                                 bool variant_w);
 hipError_t launch_layer_sumsq(const Launch& L, const float* a, const float* b, double* out);
 // variant W
 hipError_t launch_worker_moments_w(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker, int num);

@@ -760,7 +760,8 @@ __device__ __forceinline__ void fused_tile(const FusedArgs& A, const Tile& t)
             load_v<V>(A.sp.m + gi, nvalid, mv);
             load_v<V>(A.sp.v + gi, nvalid, vv);
         }
-        if (S.weight_ef) load_v<V>(A.sp.werr + gi, nvalid, wi);
+        const bool quantize_x = S.k_x >= 0;              // false: Q_x is the identity
+        if (S.weight_ef && quantize_x) load_v<V>(A.sp.werr + gi, nvalid, wi);
         float acc[V];
 #pragma unroll
         for (int j = 0; j < V; ++j) acc[j] = 0.0f;
@@ -807,14 +808,16 @@ __device__ __forceinline__ void fused_tile(const FusedArgs& A, const Tile& t)
                 xv[j] = xv[j] - u;
             }
         }
-        weight_lane<V, ROUNDING>(S, xv, wi, gi, wo, jc);
         if constexpr (!W) {
             store_v<V>(A.sp.m + gi, nvalid, mv);
             store_v<V>(A.sp.v + gi, nvalid, vv);
         }
         store_v<V>(A.sp.x + gi, nvalid, xv);
-        if (A.sp.werr) store_v<V>(A.sp.werr + gi, nvalid, wo);
-        store_wcodes<V>(A.sp.wcodes, S.wcode_bytes, gi, nvalid, jc);
+        if (quantize_x) {
+            weight_lane<V, ROUNDING>(S, xv, wi, gi, wo, jc);
+            if (A.sp.werr) store_v<V>(A.sp.werr + gi, nvalid, wo);
+            store_wcodes<V>(A.sp.wcodes, S.wcode_bytes, gi, nvalid, jc);
+        }
     }
     for (int i = 0; i < N; ++i) {
         write_pad_words(A.codes[i], t, S.code_bits);
@@ -831,6 +834,77 @@ __global__ void __launch_bounds__(kBlockThreads) k_fused(FusedArgs A)
     const Tile t = A.tiles[ti];
     if (t.flags & kTileUnaligned) fused_tile<1, ROUNDING, 1, W>(A, t);
     else fused_tile<4, ROUNDING, U, W>(A, t);
+}
+
+// ---- Q_g = identity: the messages are fp32 values ------------------------------------------------
+// W = false: the message of worker i is its gradient (plain distributed generic Adam on the mean
+// gradient, then Q_x).  W = true: second pass of variant W with the identity quantizer: the message
+// is the parked p_i = alpha m_i / sqrt(v_i + eps) + e_i, all of it is sent, so e_i <- 0.
+template <int V, int ROUNDING, int U, bool W>
+__device__ __forceinline__ void plain_tile(const FusedArgs& A, const Tile& t)
+{
+    constexpr int WAVE_ELEMS = 64 * V, BLOCK_ELEMS = (kBlockThreads / 64) * WAVE_ELEMS;
+    const StepScalars& S = A.S;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int N = S.num_workers;
+    const bool quantize_x = S.k_x >= 0;
+    for (int base = wave * WAVE_ELEMS; base < t.len; base += BLOCK_ELEMS) {
+        const int off = base + lane * V;
+        const int nvalid = min(max(t.len - off, 0), V);
+        if (nvalid == 0) continue;
+        const int64_t gi = t.start + off;
+        float xv[V], mv[V], vv[V], wi[V], wo[V], acc[V], zero[V];
+        int jc[V];
+#pragma unroll
+        for (int j = 0; j < V; ++j) { wi[j] = 0.0f; acc[j] = 0.0f; zero[j] = 0.0f; }
+        load_v<V>(A.sp.x + gi, nvalid, xv);
+        if constexpr (!W) {
+            load_v<V>(A.sp.m + gi, nvalid, mv);
+            load_v<V>(A.sp.v + gi, nvalid, vv);
+        }
+        if (S.weight_ef && quantize_x) load_v<V>(A.sp.werr + gi, nvalid, wi);
+        for (int i0 = 0; i0 < N; i0 += U) {
+            float p[U][V];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if constexpr (W) load_v<V>(A.err[i0 + u] + gi, nvalid, p[u]);
+                else load_v<V>(A.grad[i0 + u] + gi, nvalid, p[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+#pragma unroll
+                for (int j = 0; j < V; ++j) acc[j] = acc[j] + p[u][j];
+                if constexpr (W) store_v<V>(A.err[i0 + u] + gi, nvalid, zero);
+            }
+        }
+        if constexpr (W) {
+#pragma unroll
+            for (int j = 0; j < V; ++j) xv[j] = xv[j] - mean_over_workers(S, acc[j]);
+        } else {
+#pragma unroll
+            for (int j = 0; j < V; ++j) {
+                const float u = adam_step(S, mean_over_workers(S, acc[j]), mv[j], vv[j]);
+                xv[j] = xv[j] - u;
+            }
+            store_v<V>(A.sp.m + gi, nvalid, mv);
+            store_v<V>(A.sp.v + gi, nvalid, vv);
+        }
+        store_v<V>(A.sp.x + gi, nvalid, xv);
+        if (quantize_x) {
+            weight_lane<V, ROUNDING>(S, xv, wi, gi, wo, jc);
+            if (A.sp.werr) store_v<V>(A.sp.werr + gi, nvalid, wo);
+            store_wcodes<V>(A.sp.wcodes, S.wcode_bytes, gi, nvalid, jc);
+        }
+    }
+}
+
+template <int ROUNDING, int U, bool W>
+__global__ void __launch_bounds__(kBlockThreads) k_plain_messages(FusedArgs A)
+{
+    const int ti = blockIdx.x;
+    const Tile t = A.tiles[ti];
+    if (t.flags & kTileUnaligned) plain_tile<1, ROUNDING, 1, W>(A, t);
+    else plain_tile<4, ROUNDING, U, W>(A, t);
 }
 
 // ---- variant W, first pass: local moments, park p = u + e in the error buffer, scale ------------
@@ -1119,6 +1193,32 @@ static hipError_t launch_fused_any(const Launch& L, const StepScalars& S, const 
 hipError_t launch_fused(const Launch& L, const StepScalars& S, const WorkerPtrs& W, const ServerPtrs& sp)
 {
     return launch_fused_any(L, S, W, sp, false);
+}
+
+hipError_t launch_plain_messages(const Launch& L, const StepScalars& S, const WorkerPtrs& W, const ServerPtrs& sp,
+                                 bool variant_w)
+{
+    if (L.num_tiles == 0) return hipSuccess;
+    FusedArgs A;
+    A.tiles = L.tiles; A.num_tiles = L.num_tiles;
+    A.status = L.status; A.inv_scales = L.inv_scales; A.num_segments = L.num_segments; A.S = S; A.sp = sp;
+    for (int i = 0; i < QADAM_MAX_WORKERS; ++i) {
+        A.grad[i] = W.grad[i]; A.err[i] = W.err[i]; A.codes[i] = nullptr; A.scales[i] = nullptr;
+    }
+    const dim3 grid(L.num_tiles), block(kBlockThreads);
+    const bool four = S.num_workers % 4 == 0;
+#define QADAM_LAUNCH_PLAIN(R, WV)                                                                     \
+    do {                                                                                              \
+        if (four) hipLaunchKernelGGL((k_plain_messages<R, 4, WV>), grid, block, 0, L.stream, A);      \
+        else hipLaunchKernelGGL((k_plain_messages<R, 1, WV>), grid, block, 0, L.stream, A);           \
+    } while (0)
+    if (S.rounding == 0) {
+        if (variant_w) QADAM_LAUNCH_PLAIN(0, true); else QADAM_LAUNCH_PLAIN(0, false);
+    } else {
+        if (variant_w) QADAM_LAUNCH_PLAIN(1, true); else QADAM_LAUNCH_PLAIN(1, false);
+    }
+#undef QADAM_LAUNCH_PLAIN
+    return hipGetLastError();
 }
 
 hipError_t launch_fused_w(const Launch& L, const StepScalars& S, const WorkerPtrs& W, const ServerPtrs& sp)

@@ -633,3 +633,69 @@ def test_workers_on_concurrent_streams():
             assert torch.equal(a.scales[i], b.scales[i])
     assert q.get_status() == 0
     q.close()
+
+
+# --------------------------------------------- identity quantizers (settings of Theorems 1 and 2)
+@pytest.mark.parametrize("variant", ["s", "w"])
+@pytest.mark.parametrize("idg,idx", [(True, False), (False, True), (True, True)])
+def test_identity_quantizers_on_device(variant, idg, idx):
+    """k_g = QADAM_IDENTITY (full-precision messages, Theorem 2's setting), k_x = QADAM_IDENTITY
+    (full-precision weights, Theorem 1's setting), and both (plain distributed generic Adam), in the
+    whole-step calls of both variants, against the oracle's identity-quantizer steps."""
+    from paper_2004_14180_amd import QADAM_IDENTITY
+    from parity_util import close
+    k_g, k_x = (QADAM_IDENTITY if idg else 2), (QADAM_IDENTITY if idx else 6)
+    gcfg = QAdamConfig(k_g=k_g, k_x=k_x, weight_ef=1, beta1=0.9, eps=1e-6)
+    ocfg = oracle.OracleConfig(k_g=2, k_x=6, weight_ef=1, beta1=0.9, eps=1e-6,
+                               identity_g=int(idg), identity_x=int(idx))
+    sizes = RAGGED + [40000]
+    seg_off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    P, N, L = int(seg_off[-1]), 4, len(sizes)
+    rng = np.random.default_rng(300 + 2 * idg + idx)
+    q = QAdam(gcfg, seg_off, N)
+    assert (q.grad_code_bytes() == 0) == idg and (q.weight_code_bytes() == 0) == idx
+    dev = "cuda"
+    z = lambda: torch.zeros(P, device=dev)
+    x0 = (rng.standard_normal(P) * 0.02).astype(np.float32)
+    x, m, v, werr = torch.from_numpy(x0).to(dev), z(), z(), z()
+    errs, grads, mw, vw = ([z() for _ in range(N)] for _ in range(4))
+    codes = None if idg else [torch.zeros(max(q.grad_code_bytes() // 4, 1), dtype=torch.int32, device=dev) for _ in range(N)]
+    scales = None if idg else [torch.zeros(L, device=dev) for _ in range(N)]
+    wcodes = None if idx else torch.zeros(P, dtype=torch.int8, device=dev)
+    hx, hm, hv, hw = x0.copy(), np.zeros(P, np.float32), np.zeros(P, np.float32), np.zeros(P, np.float32)
+    he, hmw, hvw = ([np.zeros(P, np.float32) for _ in range(N)] for _ in range(3))
+    rep = Report()
+    for t in range(1, 5):
+        g = [(rng.standard_normal(P) * 1e-2).astype(np.float32) for _ in range(N)]
+        for i in range(N):
+            grads[i].copy_(torch.from_numpy(g[i]))
+        if variant == "s":
+            q.step_fused(t, 1e-3, 0.999, grads, None if idg else errs, codes, scales, x, m, v,
+                         None if idx else werr, wcodes)
+            out = oracle.step_s(ocfg, seg_off, t, 1e-3, 0.999, g, he, hx, hm, hv, hw)
+        else:
+            q.step_fused_w(t, 1e-3, 0.999, grads, mw, vw, errs, codes, scales, x, None if idx else werr, wcodes)
+            out = oracle.step_w(ocfg, seg_off, t, 1e-3, 0.999, g, he, hmw, hvw, hx, hw)
+        torch.cuda.synchronize()
+        close(rep, "x", x.cpu().numpy(), hx)
+        if variant == "s":
+            close(rep, "m", m.cpu().numpy(), hm); close(rep, "v", v.cpu().numpy(), hv)
+        else:
+            for i in range(N):
+                close(rep, "mw", mw[i].cpu().numpy(), hmw[i]); close(rep, "vw", vw[i].cpu().numpy(), hvw[i])
+        for i in range(N):
+            close(rep, "err", errs[i].cpu().numpy(), he[i])
+            if not idg:
+                assert np.array_equal(codes[i][: q.grad_code_bytes() // 4].cpu().numpy().view(np.uint32), out["words"][i])
+        if not idx:
+            assert np.array_equal(wcodes.cpu().numpy(), out["wcodes"])
+            close(rep, "werr", werr.cpu().numpy(), hw)
+    assert rep.float_not_bit_exact == 0 and q.get_status() == 0
+    # the calls of a quantizer that is switched off are refused
+    if idg:
+        with pytest.raises(QAdamError):
+            q.worker_quantize(0, 1, grads[0], errs[0], errs[1], errs[2])
+    if idx:
+        with pytest.raises(QAdamError):
+            q.weight_quantize(1, x, werr, errs[0])
+    q.close()

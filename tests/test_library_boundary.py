@@ -44,7 +44,7 @@ def test_bad_configs_are_rejected_on_the_host(lib):
 
     good = dict(struct_size=C.sizeof(_Config), k_g=2, k_x=6, rounding=0, weight_ef=1, adam_flavor=0,
                 beta1=0.9, eps=1e-8, seed=0)
-    for bad in [dict(struct_size=4), dict(k_g=-1), dict(k_g=7), dict(k_x=15), dict(rounding=2),
+    for bad in [dict(struct_size=4), dict(k_g=-2), dict(k_g=7), dict(k_x=15), dict(k_x=-2), dict(rounding=2),
                 dict(weight_ef=3), dict(beta1=1.0), dict(eps=-1.0)]:
         cfg = _Config(**{**good, **bad})
         assert init(cfg) == -1, bad

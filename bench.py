@@ -8,6 +8,11 @@ qadam_step_fused over one batch of synthetic gradients that is already resident 
 Prints ONE JSON line: parameters updated per second (value), ms per step, the HBM roofline of the
 dominant kernel (the fused main pass, timed with HIP events inside the library on the stream it is
 launched on) and the CPU oracle timed on a bounded sample of the same workload.
+
+The step is timed with the library's filtered scale pass (qadam_trust_error_buffers: the error
+buffers belong to the optimizer between steps, so the scales, bit for bit the same, need e only
+where |g| can still reach the layer's maximum); the same number of steps is then timed with the
+option off and reported beside it (config.same_steps_with_full_scale_pass).
 """
 import argparse
 import json
@@ -205,6 +210,10 @@ def main():
     ap.add_argument("--rounding", type=int, choices=[0, 1], default=0,
                     help="0: nearest (the paper's quantizers, the headline); 1: unbiased stochastic rounding "
                          "driven by Philox4x32-10")
+    ap.add_argument("--scale-pass", choices=["full", "filtered"], default="filtered",
+                    help="full: the scale pass reads g and e of every element; filtered: "
+                         "qadam_trust_error_buffers(1), it reads e only where |g| can still reach the layer's "
+                         "maximum (same results; the error buffers are the library's between steps)")
     ap.add_argument("--k-g", type=int, default=None,
                     help="override the workload's gradient grid (0: 2-bit codes, 1-2: 3-bit, 3-6: 4-bit, "
                          "-1: no gradient quantization)")
@@ -243,6 +252,8 @@ def main():
                       eps=wl.eps)
     q = QAdam(cfg, wl.seg_offsets, N)
     q.profile_enable(True)
+    if args.scale_pass == "filtered":
+        q.trust_error_buffers(True)
     code_bits = q.grad_code_bytes() * 8.0 / P
     wcode_bytes = q.weight_code_bytes() / P
 
@@ -277,20 +288,39 @@ def main():
             sys.exit("bench.py: --path calls is for variant S")
         return bench_calls(args, wl, q, grads, errs, codes, scales, x, m, v, werr, wcodes, code_bits, wcode_bytes)
 
-    step_ms, scale_ms, main_ms = [], [], []
-    for t in range(1, args.warmup + args.steps + 1):
-        wl.fill_gradients(t, grads)            # untimed: inputs are resident before the clock starts
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        if args.variant == "s":
-            q.step_fused(t, wl.lr, wl.beta2, grads, errs, codes, scales, x, m, v, werr, wcodes)
-        else:
-            q.step_fused_w(t, wl.lr, wl.beta2, grads, mw, vw, errs, codes, scales, x, werr, wcodes)
-        torch.cuda.synchronize()
-        dt = (time.perf_counter() - t0) * 1e3
-        a, b = q.profile_read()
-        if t > args.warmup:
-            step_ms.append(dt); scale_ms.append(a); main_ms.append(b)
+    def timed_steps(first, warmup, steps):
+        """`warmup` untimed then `steps` timed steps; each timed between two device synchronisations,
+        with the step's gradients already resident.  Returns per-step (wall, scale pass, main pass) ms."""
+        out = []
+        for t in range(first, first + warmup + steps):
+            wl.fill_gradients(t, grads)        # untimed: inputs are resident before the clock starts
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            if args.variant == "s":
+                q.step_fused(t, wl.lr, wl.beta2, grads, errs, codes, scales, x, m, v, werr, wcodes)
+            else:
+                q.step_fused_w(t, wl.lr, wl.beta2, grads, mw, vw, errs, codes, scales, x, werr, wcodes)
+            torch.cuda.synchronize()
+            dt = (time.perf_counter() - t0) * 1e3
+            a, b = q.profile_read()
+            if t >= first + warmup:
+                out.append((dt, a, b))
+        return out
+
+    # the library applies the filter from about four million worker-elements on (4096 tiles of 4096)
+    tiles = sum((n + 4095) // 4096 for n in wl.sizes)
+    filtered = args.scale_pass == "filtered" and args.variant == "s" and wl.k_g >= 0 and tiles * N >= 4096
+    res = timed_steps(1, args.warmup, args.steps)
+    step_ms, scale_ms, main_ms = ([r[k] for r in res] for k in range(3))
+    full_pass = None
+    if filtered:
+        # the same steps once more with the option off (every element's g and e read for the scales)
+        q.trust_error_buffers(False)
+        res_full = timed_steps(1 + args.warmup + args.steps, 1, args.steps)
+        full_ms = sum(r[0] for r in res_full) / len(res_full)
+        full_pass = {"ms_per_step": round(full_ms, 4), "value": P / (full_ms * 1e-3),
+                     "scale_pass_ms": round(sum(r[1] for r in res_full) / len(res_full), 4),
+                     "main_pass_ms": round(sum(r[2] for r in res_full) / len(res_full), 4)}
     if os.environ.get("QADAM_BENCH_VERBOSE"):
         print("per-step main ms:", [round(v_, 2) for v_ in main_ms], file=sys.stderr)
         print("per-step scale ms:", [round(v_, 2) for v_ in scale_ms], file=sys.stderr)
@@ -314,7 +344,8 @@ def main():
                                     "achieved": round(a_second * P / (main_avg * 1e-3) / 1e9, 1)},
                     "whole_step_GBs": round((a_first + a_second) * P / (ms_per_step * 1e-3) / 1e9, 1)}
     a_main = algorithmic_bytes_per_param(N, code_bits, wcode_bytes, weight_ef)
-    a_scale = 8.0 * N if code_bits else 0.0
+    # scale pass: g and e of every worker; filtered: g, plus e of the few elements that can be the maximum
+    a_scale = (4.0 if filtered else 8.0) * N if code_bits else 0.0
     achieved = a_main * P / (main_avg * 1e-3) / 1e9
     roofline_s = {"bound": "hbm", "kernel": "k_fused (main pass of qadam_step_fused)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -323,7 +354,8 @@ def main():
                 if args.shrink == 1 and args.k_g is None and args.k_x is None and args.rounding == 0 else None,
                 "algorithmic_bytes_per_param": a_main,
                 "avg_launch_ms": round(main_avg, 4),
-                "scale_pass": {"algorithmic_bytes_per_param": a_scale, "avg_launch_ms": round(scale_avg, 4),
+                "scale_pass": {"mode": "filtered" if filtered else "full", "algorithmic_bytes_per_param": a_scale,
+                               "avg_launch_ms": round(scale_avg, 4),
                                "achieved": round(a_scale * P / (max(scale_avg, 1e-6) * 1e-3) / 1e9, 1)},
                 "whole_step_GBs": round((a_main + a_scale) * P / (ms_per_step * 1e-3) / 1e9, 1)}
     if args.variant == "s":
@@ -346,6 +378,9 @@ def main():
                    "worker_elements_per_s": N * P / (ms_per_step * 1e-3),
                    "resident_bytes": sum(working_set),
                    "allocator_conditioning_cycles": args.alloc_cycles,
+                   "scale_pass": "filtered: exact scales, e read only where |g| can reach the layer maximum "
+                                 "(qadam_trust_error_buffers)" if filtered else "full: g and e of every element",
+                   "same_steps_with_full_scale_pass": full_pass,
                    "status_word": status},
         "roofline": roofline,
     }

@@ -186,6 +186,22 @@ int qadam_step_fused_w(qadam_handle_t h, int64_t step, float lr, float beta2,
 int qadam_weight_dequantize(qadam_handle_t h, const void* wcodes_dev, float* xhat_dev, void* stream);
 int qadam_weight_dequantize_f16(qadam_handle_t h, const void* wcodes_dev, void* xhat_dev, void* stream);
 
+/* Opt-in: let qadam_step_fused skip most of the first read of the error buffers.
+ * The per-layer scale ||g_i + e_i||_inf normally costs one full read of g_i and e_i before the main pass.
+ * The quantizer bounds the residual it leaves (|e| <= s/4 per element for k_g >= 1 with nearest rounding,
+ * s/2 for the ternary grid, twice that with stochastic rounding), so when e_i is exactly what the previous
+ * step of this handle wrote, an element whose |g| lies more than that bound below a known lower bound of the
+ * scale cannot be the maximum.  With the option on the scale pass takes the exact maxima of a sample of tiles as
+ * that lower bound and then reads e only where |g| is large enough to matter; the scales (and so every
+ * output) are the same bits as without the option.  On Gaussian-like gradients this halves the scale
+ * pass; on heavy-tailed ones it falls back to reading everything, layer by layer.
+ * CONTRACT with the option on: between two step calls the caller must not change errs[i] (or must call this
+ * function again, which makes the next step read everything).  The first step after qadam_init, or after
+ * this call, always reads everything.  Violating the contract gives scales that are too small.
+ * on = 1 uses the filtered pass only where it pays (it adds two small launches: from about four
+ * million worker-elements on); on = 2 uses it always; on = 0 (the default) never. */
+int qadam_trust_error_buffers(qadam_handle_t h, int32_t on);
+
 /* Diagnostic: per-layer squared Euclidean norms  out[l] = sum_{j in layer l} (a_j + b_j)^2, with the sum
  * a_j + b_j taken in fp32 (as the step forms g + e) and squares and sums in fp64 in a fixed order, so the
  * result is the same bits on every run.  b_dev may be NULL (then a alone).  out_dev: L doubles (device).

@@ -23,7 +23,7 @@ EXPORTS = [
     "qadam_init", "qadam_destroy", "qadam_grad_code_bytes", "qadam_weight_code_bytes",
     "qadam_num_params", "qadam_worker_quantize", "qadam_server_step", "qadam_weight_quantize",
     "qadam_step_fused", "qadam_worker_step_w", "qadam_server_apply_w", "qadam_step_fused_w", "qadam_weight_dequantize",
-    "qadam_weight_dequantize_f16", "qadam_layer_sumsq",
+    "qadam_weight_dequantize_f16", "qadam_layer_sumsq", "qadam_trust_error_buffers",
     "qadam_get_status", "qadam_last_error", "qadam_profile_enable", "qadam_profile_read",
 ]
 
@@ -102,6 +102,7 @@ def load_library():
     lib.qadam_weight_dequantize.argtypes = [vp, vp, vp, vp]
     lib.qadam_weight_dequantize_f16.argtypes = [vp, vp, vp, vp]
     lib.qadam_layer_sumsq.argtypes = [vp, vp, vp, vp, vp]
+    lib.qadam_trust_error_buffers.argtypes = [vp, i32]
     lib.qadam_get_status.argtypes = [vp, C.POINTER(_Status), i32, vp]
     lib.qadam_last_error.restype = C.c_char_p
     lib.qadam_profile_enable.argtypes = [vp, i32]
@@ -226,6 +227,11 @@ class QAdam:
     def layer_sumsq(self, a, b, out, stream=None):
         """out[l] = sum over layer l of (a + b)^2 in fp64 (b may be None)."""
         self._check(self._lib.qadam_layer_sumsq(self._h, _ptr(a), _ptr(b), _ptr(out), _stream(stream)))
+
+    def trust_error_buffers(self, on=1):
+        """Opt in to the filtered scale pass (see include/qadam.h for the contract):
+        0 off, 1 where it pays, 2 always."""
+        self._check(self._lib.qadam_trust_error_buffers(self._h, int(on)))
 
     def profile_enable(self, on=True):
         self._check(self._lib.qadam_profile_enable(self._h, int(on)))

@@ -27,6 +27,12 @@ struct qadam_ctx {
     uint32_t* d_tile_max;       // [num_workers][num_tiles]
     int32_t*  d_seg_tile_begin; // [num_segments + 1]
     double*   d_tile_sum;       // [num_tiles]
+    float*    d_err_bound;      // [num_workers][num_segments]
+    uint32_t* d_thr;            // [num_workers][num_segments]
+    int32_t*  d_sample_tiles;   // indices of the sampled tiles
+    int32_t   num_sample_tiles;
+    int       trust_errs;                       // qadam_trust_error_buffers: 0 off, 1 when it pays, 2 always
+    bool      bound_valid[QADAM_MAX_WORKERS];   // d_err_bound row i describes what errs[i] now holds
     bool       profile;
     bool       profile_valid;
     hipEvent_t ev[3];
@@ -110,6 +116,8 @@ Launch make_launch(const qadam_ctx* h, void* stream)
     Launch L;
     L.tiles = h->d_tiles; L.inv_scales = h->d_inv_scales;
     L.tile_max = h->d_tile_max; L.seg_tile_begin = h->d_seg_tile_begin; L.tile_sum = h->d_tile_sum;
+    L.err_bound = h->d_err_bound; L.thr = h->d_thr;
+    L.sample_tiles = h->d_sample_tiles; L.num_sample_tiles = h->num_sample_tiles;
     L.num_tiles = h->num_tiles; L.num_segments = h->num_segments;
     L.num_params = h->num_params; L.status = h->d_status; L.stream = static_cast<hipStream_t>(stream);
     return L;
@@ -219,6 +227,7 @@ int qadam_init(qadam_handle_t* out, const qadam_config_t* cfg, const int64_t* se
     // tile table: segments cut into runs of tile_elems elements
     std::vector<Tile> tiles;
     tiles.reserve((size_t)tile_count);
+    std::vector<int32_t> sample_tiles;
     std::vector<int32_t> seg_tile_begin(num_segments + 1, 0);
     int64_t word_off = 0;
     for (int l = 0; l < num_segments; ++l) {
@@ -234,6 +243,10 @@ int qadam_init(qadam_handle_t* out, const qadam_config_t* cfg, const int64_t* se
             t.seg = l;
             t.flags = (a % 4 != 0) ? kTileUnaligned : 0;
             if (o + h->tile_elems >= n) t.flags |= (int32_t)(seg_words - used_words) << 8;
+            if ((o / h->tile_elems) % kSampleStride == 0) {
+                t.flags |= kTileSampled;
+                sample_tiles.push_back((int32_t)tiles.size());
+            }
             t.reserved = 0;
             tiles.push_back(t);
         }
@@ -243,6 +256,7 @@ int qadam_init(qadam_handle_t* out, const qadam_config_t* cfg, const int64_t* se
 
     seg_tile_begin[num_segments] = (int32_t)tiles.size();
     h->num_tiles = (int32_t)tiles.size();
+    h->num_sample_tiles = (int32_t)sample_tiles.size();
 
     hipError_t e = hipGetDevice(&h->device);
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&h->d_status), 256);
@@ -256,6 +270,16 @@ int qadam_init(qadam_handle_t* out, const qadam_config_t* cfg, const int64_t* se
         e = hipMalloc(reinterpret_cast<void**>(&h->d_tile_max), sizeof(uint32_t) * (size_t)h->num_tiles * num_workers);
     if (e == hipSuccess && h->num_tiles > 0)
         e = hipMalloc(reinterpret_cast<void**>(&h->d_tile_sum), sizeof(double) * (size_t)h->num_tiles);
+    if (e == hipSuccess && num_segments > 0)
+        e = hipMalloc(reinterpret_cast<void**>(&h->d_err_bound), sizeof(float) * (size_t)num_segments * num_workers);
+    if (e == hipSuccess && num_segments > 0)
+        e = hipMalloc(reinterpret_cast<void**>(&h->d_thr), sizeof(uint32_t) * (size_t)num_segments * num_workers);
+    if (e == hipSuccess && h->num_sample_tiles > 0) {
+        e = hipMalloc(reinterpret_cast<void**>(&h->d_sample_tiles), sizeof(int32_t) * sample_tiles.size());
+        if (e == hipSuccess)
+            e = hipMemcpy(h->d_sample_tiles, sample_tiles.data(), sizeof(int32_t) * sample_tiles.size(),
+                          hipMemcpyHostToDevice);
+    }
     if (e == hipSuccess && h->num_tiles > 0) {
         e = hipMalloc(reinterpret_cast<void**>(&h->d_tiles), sizeof(Tile) * tiles.size());
         if (e == hipSuccess)
@@ -268,6 +292,9 @@ int qadam_init(qadam_handle_t* out, const qadam_config_t* cfg, const int64_t* se
         if (h->d_tile_max) (void)hipFree(h->d_tile_max);
         if (h->d_seg_tile_begin) (void)hipFree(h->d_seg_tile_begin);
         if (h->d_tile_sum) (void)hipFree(h->d_tile_sum);
+        if (h->d_err_bound) (void)hipFree(h->d_err_bound);
+        if (h->d_thr) (void)hipFree(h->d_thr);
+        if (h->d_sample_tiles) (void)hipFree(h->d_sample_tiles);
         delete h;
         return hip_fail(e, "qadam_init device tables");
     }
@@ -286,6 +313,9 @@ int qadam_destroy(qadam_handle_t h)
     if (h->d_tile_max) (void)hipFree(h->d_tile_max);
     if (h->d_seg_tile_begin) (void)hipFree(h->d_seg_tile_begin);
     if (h->d_tile_sum) (void)hipFree(h->d_tile_sum);
+    if (h->d_err_bound) (void)hipFree(h->d_err_bound);
+    if (h->d_thr) (void)hipFree(h->d_thr);
+    if (h->d_sample_tiles) (void)hipFree(h->d_sample_tiles);
     delete h;
     return QADAM_OK;
 }
@@ -313,8 +343,9 @@ int qadam_worker_quantize(qadam_handle_t h, int32_t worker, int64_t step, const 
     const StepScalars S = make_scalars(h, step, 0.0f, 0.0f);
     const Launch L = make_launch(h, stream);
     QADAM_HIP(launch_amax(L, S, W, worker, 1));
-    QADAM_HIP(launch_reduce_scales(L, W, worker, 1));
+    QADAM_HIP(launch_reduce_scales(L, S, W, worker, 1));
     QADAM_HIP(launch_worker_quantize(L, S, W, worker));
+    h->bound_valid[worker] = true;
     return QADAM_OK;
 }
 
@@ -399,8 +430,14 @@ int qadam_step_fused(qadam_handle_t h, int64_t step, float lr, float beta2, cons
     const Launch L = make_launch(h, stream);
     if (h->profile) QADAM_HIP(hipEventRecord(h->ev[0], L.stream));
     if (!idg) {
-        QADAM_HIP(launch_amax(L, S, W, 0, h->num_workers));
-        QADAM_HIP(launch_reduce_scales(L, W, 0, h->num_workers));
+        // the filtered pass costs two more (small) launches: only worth it beyond a few million worker-elements
+        bool filtered = h->trust_errs == 2 ||
+                        (h->trust_errs == 1 && (int64_t)h->num_tiles * h->num_workers >= 4096);
+        for (int i = 0; i < h->num_workers; ++i) filtered = filtered && h->bound_valid[i];
+        if (filtered) QADAM_HIP(launch_amax_filtered(L, S, W, 0, h->num_workers));
+        else QADAM_HIP(launch_amax(L, S, W, 0, h->num_workers));
+        QADAM_HIP(launch_reduce_scales(L, S, W, 0, h->num_workers));
+        for (int i = 0; i < h->num_workers; ++i) h->bound_valid[i] = true;
     }
     if (h->profile) QADAM_HIP(hipEventRecord(h->ev[1], L.stream));
     if (idg) QADAM_HIP(launch_plain_messages(L, S, W, sp, false));
@@ -435,7 +472,8 @@ int qadam_worker_step_w(qadam_handle_t h, int32_t worker, int64_t step, float lr
     const Launch L = make_launch(h, stream);
     // pass 1: local moments, p = alpha m / sqrt(v + eps) + e parked in the error buffer, tile maxima
     QADAM_HIP(launch_worker_moments_w(L, S, W, worker, 1));
-    QADAM_HIP(launch_reduce_scales(L, W, worker, 1));
+    QADAM_HIP(launch_reduce_scales(L, S, W, worker, 1));
+    h->bound_valid[worker] = true;
     // pass 2: quantize the parked p
     W.grad[worker] = nullptr;
     QADAM_HIP(launch_worker_quantize(L, S, W, worker));
@@ -469,7 +507,8 @@ int qadam_step_fused_w(qadam_handle_t h, int64_t step, float lr, float beta2, co
     if (h->profile) QADAM_HIP(hipEventRecord(h->ev[0], L.stream));
     // pass 1 (all workers): local moments, p parked in the error buffers, tile maxima; then scales
     QADAM_HIP(launch_worker_moments_w(L, S, W, 0, h->num_workers));
-    if (!idg) QADAM_HIP(launch_reduce_scales(L, W, 0, h->num_workers));
+    if (!idg) QADAM_HIP(launch_reduce_scales(L, S, W, 0, h->num_workers));
+    for (int i = 0; i < h->num_workers; ++i) h->bound_valid[i] = !idg;
     if (h->profile) QADAM_HIP(hipEventRecord(h->ev[1], L.stream));
     // pass 2: quantize every worker's parked p, subtract the mean message, Q_x
     if (idg) QADAM_HIP(launch_plain_messages(L, S, W, sp, true));
@@ -503,6 +542,15 @@ int qadam_layer_sumsq(qadam_handle_t h, const float* a_dev, const float* b_dev, 
     QADAM_CHECK(check_ptr(b_dev, "b_dev", false));
     QADAM_CHECK(check_ptr(out_dev, "out_dev", h->num_segments > 0));
     QADAM_HIP(launch_layer_sumsq(make_launch(h, stream), a_dev, b_dev, out_dev));
+    return QADAM_OK;
+}
+
+int qadam_trust_error_buffers(qadam_handle_t h, int32_t on)
+{
+    QADAM_CHECK(check_handle(h));
+    if (on < 0 || on > 2) return fail(QADAM_EINVAL, "on must be 0, 1 or 2");
+    h->trust_errs = on;
+    for (bool& b : h->bound_valid) b = false;     // the next step reads everything and starts the record
     return QADAM_OK;
 }
 

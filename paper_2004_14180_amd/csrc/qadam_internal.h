@@ -18,12 +18,15 @@ struct Tile {
     int32_t len;        // elements in the tile (1 .. tile_elems)
     int32_t seg;        // layer segment the tile belongs to
     int32_t flags;      // bit 0: start is not a multiple of 4 (no 128-bit accesses);
+                        // bit 1: sampled tile of the filtered scale pass;
                         // bits 8..9: zero words to append after the tile's codes (segment padding)
     int32_t reserved;
 };
 static_assert(sizeof(Tile) == 32, "tile records are read as two 128-bit scalar loads");
 
 constexpr int kTileUnaligned = 1;
+constexpr int kTileSampled = 2;
+constexpr int kSampleStride = 64;   // every 64th tile of a layer (from its first) is a sampled tile
 constexpr int kBlockThreads = 256;
 
 // Scalars of one launch, identical for every kernel.
@@ -69,6 +72,10 @@ struct Launch {
     int32_t     num_segments;
     int64_t     num_params;
     double*     tile_sum;   // device, [num_tiles]: per-tile partial sums of the norm diagnostic
+    float*      err_bound;  // device, [num_workers][num_segments]: bound on |e| left by the last step
+    uint32_t*   thr;        // device, [num_workers][num_segments]: thresholds of the filtered scale pass
+    const int32_t* sample_tiles;    // device: indices of the sampled tiles
+    int32_t     num_sample_tiles;
     uint32_t*   status;     // device status word
     hipStream_t stream;
 };
@@ -77,7 +84,8 @@ struct Launch {
 // scales in two stages without atomics: per-tile maxima, then one workgroup per (worker, layer)
 // reduces its tiles and also writes the reciprocal used by the fast quotient
 hipError_t launch_amax(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker, int num);
-hipError_t launch_reduce_scales(const Launch& L, const WorkerPtrs& W, int first_worker, int num);
+hipError_t launch_reduce_scales(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker, int num);
+hipError_t launch_amax_filtered(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker, int num);
 hipError_t launch_worker_quantize(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int worker);
 hipError_t launch_server_step(const Launch& L, const StepScalars& S, const WorkerPtrs& W, const ServerPtrs& sp);
 hipError_t launch_weight_quantize(const Launch& L, const StepScalars& S, const float* x, float* werr, void* wcodes);

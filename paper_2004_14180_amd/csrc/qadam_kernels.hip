@@ -399,6 +399,9 @@ struct AmaxArgs {
     const float* err[QADAM_MAX_WORKERS];
     uint32_t* tile_max;     // [N][num_tiles]
     int first_worker;
+    const int32_t* tile_list;   // null: workgroup b takes tile b; else tile tile_list[b] (the sampled tiles)
+    const uint32_t* thr;        // filtered pass only: [N][L] thresholds on |g| as bit patterns (0: read everything)
+    int num_segments;
 };
 
 struct FusedArgs {
@@ -434,6 +437,10 @@ struct ScaleArgs {
     const uint32_t* tile_max;
     const int32_t* seg_tile_begin;
     int first_worker, num_segments, num_tiles;
+    float* err_bound;       // [N][L]: bound on |e'| after the step that uses these scales
+    uint32_t* thr;          // [N][L]: thresholds of the filtered pass (written by k_reduce_lower_bounds)
+    float bound_factor;     // |e'| <= bound_factor * s for this quantizer and rounding mode
+    int sample_stride;      // every sample_stride-th tile of a layer is a sampled tile
 };
 
 // ------------------------------------------------------------------------------------------------
@@ -482,6 +489,34 @@ __global__ void __launch_bounds__(kBlockThreads) k_reduce_scales(ScaleArgs A)
         // 1/s must be a normal number with full precision for the error bound of the fast quotient
         const bool ok = s >= 0x1p-100f && s <= 0x1p100f;
         A.inv_scales[(size_t)w * A.num_segments + l] = ok ? 1.0f / s : 0.0f;
+        // what the residual p - Q_g(p) of this step can reach (a non-finite scale gives a non-finite
+        // bound, which switches the next step's filter off)
+        A.err_bound[(size_t)w * A.num_segments + l] = s * A.bound_factor;
+    }
+}
+
+// Filtered scale pass, stage 2 of 4.  grid: (layers, workers).  The sampled tiles (every
+// sample_stride-th of a layer) have their exact maxima: their max is a lower bound LB of the
+// layer's scale.  With |e_j| <= B (the bound left by the previous step), an element with
+// |g_j| < LB - B has |g_j + e_j| < LB and cannot be the maximum, so the next stage reads e only
+// where |g_j| >= thr = (LB - B) minus a safety margin that covers the rounding of g + e.
+__global__ void __launch_bounds__(kBlockThreads) k_reduce_lower_bounds(ScaleArgs A)
+{
+    const int l = blockIdx.x, w = A.first_worker + blockIdx.y;
+    const int t0 = A.seg_tile_begin[l], t1 = A.seg_tile_begin[l + 1];
+    const uint32_t* part = A.tile_max + (size_t)w * A.num_tiles;
+    uint32_t local = 0;
+    for (int t = t0 + (int)threadIdx.x * A.sample_stride; t < t1; t += kBlockThreads * A.sample_stride) {
+        const uint32_t v = part[t];
+        local = v > local ? v : local;
+    }
+    const uint32_t bm = block_max(local);
+    if (threadIdx.x == 0) {
+        const float lb = u2f(bm);
+        const float bound = A.err_bound[(size_t)w * A.num_segments + l];
+        const float thr = (lb - bound * 1.001f) * 0.999f;
+        const bool usable = thr > 0.0f && thr < __builtin_inff() && lb < __builtin_inff();
+        A.thr[(size_t)w * A.num_segments + l] = usable ? f2u(thr) : 0u;
     }
 }
 
@@ -526,7 +561,7 @@ __device__ __forceinline__ uint32_t amax_tile(const float* __restrict__ g, const
 // grid: (tiles, workers)
 __global__ void __launch_bounds__(kBlockThreads) k_amax(AmaxArgs A)
 {
-    const int ti = blockIdx.x;
+    const int ti = A.tile_list ? A.tile_list[blockIdx.x] : (int)blockIdx.x;
     const Tile t = A.tiles[ti];
     const int w = A.first_worker + blockIdx.y;
     const float* g = A.grad[w];
@@ -534,6 +569,85 @@ __global__ void __launch_bounds__(kBlockThreads) k_amax(AmaxArgs A)
     uint32_t local;
     if (t.flags & kTileUnaligned) local = amax_tile<1>(g, e, t);
     else local = amax_tile<4>(g, e, t);
+    const uint32_t bm = block_max(local);
+    if (threadIdx.x == 0) A.tile_max[(size_t)w * A.num_tiles + ti] = bm;
+}
+
+// Filtered scale pass, stage 3 of 4: max |g + e| over the elements of a tile that can still be the
+// layer's maximum, i.e. those with |g| >= thr; e is read for those only.  Comparing bit patterns
+// makes a NaN or Inf in g a candidate, so it still surfaces in the scale.
+template <int V>
+__device__ __forceinline__ uint32_t amax_tile_filtered(const float* __restrict__ g, const float* __restrict__ e,
+                                                       const Tile& t, uint32_t thr)
+{
+    constexpr int BLOCK_ELEMS = kBlockThreads * V;
+    uint32_t local = 0;
+    if constexpr (V == 4) {
+        if (t.len == 4 * BLOCK_ELEMS) {
+            float gv[4][4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) load_v<4>(g + t.start + k * BLOCK_ELEMS + threadIdx.x * 4, 4, gv[k]);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                uint32_t top = 0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t ab = f2u(gv[k][j]) & 0x7fffffffu;
+                    top = ab > top ? ab : top;
+                }
+                if (top >= thr) {
+                    float ev[4];
+                    load_v<4>(e + t.start + k * BLOCK_ELEMS + threadIdx.x * 4, 4, ev);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const uint32_t ab = f2u(gv[k][j] + ev[j]) & 0x7fffffffu;
+                        local = ab > local ? ab : local;
+                    }
+                }
+            }
+            return local;
+        }
+    }
+    for (int off = threadIdx.x * V; off < t.len; off += BLOCK_ELEMS) {
+        const int nvalid = min(t.len - off, V);
+        float gv[V], ev[V];
+        load_v<V>(g + t.start + off, nvalid, gv);
+        uint32_t top = 0;
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            const uint32_t ab = f2u(gv[j]) & 0x7fffffffu;
+            top = ab > top ? ab : top;
+        }
+        if (top >= thr) {
+            load_v<V>(e + t.start + off, nvalid, ev);
+#pragma unroll
+            for (int j = 0; j < V; ++j) {
+                const uint32_t ab = f2u(gv[j] + ev[j]) & 0x7fffffffu;
+                local = ab > local ? ab : local;
+            }
+        }
+    }
+    return local;
+}
+
+// grid: (tiles, workers).  Sampled tiles keep the exact maximum stage 1 stored for them.
+__global__ void __launch_bounds__(kBlockThreads) k_amax_filtered(AmaxArgs A)
+{
+    const int ti = blockIdx.x;
+    const Tile t = A.tiles[ti];
+    if (t.flags & kTileSampled) return;
+    const int w = A.first_worker + blockIdx.y;
+    const float* g = A.grad[w];
+    const float* e = A.err[w];
+    const uint32_t thr = A.thr[(size_t)w * A.num_segments + t.seg];
+    uint32_t local;
+    if (thr == 0u) {
+        if (t.flags & kTileUnaligned) local = amax_tile<1>(g, e, t);
+        else local = amax_tile<4>(g, e, t);
+    } else {
+        if (t.flags & kTileUnaligned) local = amax_tile_filtered<1>(g, e, t, thr);
+        else local = amax_tile_filtered<4>(g, e, t, thr);
+    }
     const uint32_t bm = block_max(local);
     if (threadIdx.x == 0) A.tile_max[(size_t)w * A.num_tiles + ti] = bm;
 }
@@ -1050,15 +1164,41 @@ int grid_for(int64_t work_items, int per_block)
 // ================================================================================================
 // launchers
 // ================================================================================================
-hipError_t launch_reduce_scales(const Launch& L, const WorkerPtrs& W, int first_worker, int num)
+// |p - Q_g(p)| <= factor * s: half the widest gap of the grid for nearest rounding (the gap between
+// 1/2 and 1, or between 0 and 1 for the ternary grid), the whole gap for stochastic rounding; the
+// small excess covers the rounding of the quotient p / s that takes the decision.
+static float residual_bound_factor(const StepScalars& S)
 {
-    if (L.num_segments == 0 || num == 0) return hipSuccess;
-    ScaleArgs A;
+    const float half_gap = S.k_g >= 1 ? 0.25f : 0.5f;
+    return (S.rounding == 0 ? half_gap : 2.0f * half_gap) * (1.0f + 0x1p-20f);
+}
+
+static void fill_scale_args(ScaleArgs& A, const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker)
+{
     for (int i = 0; i < QADAM_MAX_WORKERS; ++i) A.scales[i] = W.scales[i];
     A.inv_scales = L.inv_scales; A.tile_max = L.tile_max; A.seg_tile_begin = L.seg_tile_begin;
     A.first_worker = first_worker; A.num_segments = L.num_segments; A.num_tiles = L.num_tiles;
+    A.err_bound = L.err_bound; A.thr = L.thr;
+    A.bound_factor = residual_bound_factor(S);
+    A.sample_stride = kSampleStride;
+}
+
+hipError_t launch_reduce_scales(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker, int num)
+{
+    if (L.num_segments == 0 || num == 0) return hipSuccess;
+    ScaleArgs A;
+    fill_scale_args(A, L, S, W, first_worker);
     hipLaunchKernelGGL(k_reduce_scales, dim3(L.num_segments, num), dim3(kBlockThreads), 0, L.stream, A);
     return hipGetLastError();
+}
+
+static void fill_amax_args(AmaxArgs& A, const Launch& L, const WorkerPtrs& W, int first_worker)
+{
+    A.tiles = L.tiles; A.num_tiles = L.num_tiles;
+    for (int i = 0; i < QADAM_MAX_WORKERS; ++i) { A.grad[i] = W.grad[i]; A.err[i] = W.err[i]; }
+    A.tile_max = L.tile_max;
+    A.first_worker = first_worker;
+    A.tile_list = nullptr; A.thr = L.thr; A.num_segments = L.num_segments;
 }
 
 hipError_t launch_amax(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker, int num)
@@ -1066,11 +1206,26 @@ hipError_t launch_amax(const Launch& L, const StepScalars& S, const WorkerPtrs& 
     (void)S;
     if (L.num_tiles == 0 || num == 0) return hipSuccess;
     AmaxArgs A;
-    A.tiles = L.tiles; A.num_tiles = L.num_tiles;
-    for (int i = 0; i < QADAM_MAX_WORKERS; ++i) { A.grad[i] = W.grad[i]; A.err[i] = W.err[i]; }
-    A.tile_max = L.tile_max;
-    A.first_worker = first_worker;
+    fill_amax_args(A, L, W, first_worker);
     hipLaunchKernelGGL(k_amax, dim3(L.num_tiles, num), dim3(kBlockThreads), 0, L.stream, A);
+    return hipGetLastError();
+}
+
+// The scale pass when every |e_j| is known to be at most the bound the previous step left:
+// exact maxima of the sampled tiles -> per-layer thresholds -> the other tiles, reading e only
+// where |g| reaches the threshold.  launch_reduce_scales follows as usual.
+hipError_t launch_amax_filtered(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker, int num)
+{
+    if (L.num_tiles == 0 || num == 0) return hipSuccess;
+    AmaxArgs A;
+    fill_amax_args(A, L, W, first_worker);
+    A.tile_list = L.sample_tiles;
+    hipLaunchKernelGGL(k_amax, dim3(L.num_sample_tiles, num), dim3(kBlockThreads), 0, L.stream, A);
+    ScaleArgs R;
+    fill_scale_args(R, L, S, W, first_worker);
+    hipLaunchKernelGGL(k_reduce_lower_bounds, dim3(L.num_segments, num), dim3(kBlockThreads), 0, L.stream, R);
+    A.tile_list = nullptr;
+    hipLaunchKernelGGL(k_amax_filtered, dim3(L.num_tiles, num), dim3(kBlockThreads), 0, L.stream, A);
     return hipGetLastError();
 }
 

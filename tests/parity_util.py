@@ -222,7 +222,7 @@ def compare_step(rep: Report, ocfg, seg_off, ds: DeviceState, hs: HostState, out
 
 def run_workload_parity(wl, steps, fused=True, k_g=None, k_x=None, rounding=0, weight_ef=None,
                         adam_flavor=0, seed=0, gen_device="cpu", threads=THREADS, check_every=1,
-                        progress=None):
+                        progress=None, trust_errs=False):
     """Run `steps` steps of a workload on the GPU and in the oracle, comparing after each step."""
     k_g = wl.k_g if k_g is None else k_g
     k_x = wl.k_x if k_x is None else k_x
@@ -231,6 +231,8 @@ def run_workload_parity(wl, steps, fused=True, k_g=None, k_x=None, rounding=0, w
                          beta1=wl.beta1, eps=wl.eps, seed=seed)
     seg_off = wl.seg_offsets
     q = QAdam(gcfg, seg_off, wl.num_workers)
+    if trust_errs:
+        q.trust_error_buffers(2)        # filtered scale pass from the second step on
     x0 = wl.init_weights(gen_device)
     ds = DeviceState(q, x0)
     hs = HostState(wl.num_params, wl.num_workers, x0.cpu().numpy())

@@ -36,6 +36,8 @@ class FullRun:
         self.gcfg, self.ocfg = configs(k_g=wl.k_g, k_x=wl.k_x, weight_ef=1, beta1=wl.beta1, eps=wl.eps)
         self.seg = wl.seg_offsets
         self.q = QAdam(self.gcfg, self.seg, wl.num_workers)
+        # as the benchmark runs it: from the second step of a handle on, the scale pass is the filtered one
+        self.q.trust_error_buffers(True)
         P, N = wl.num_params, wl.num_workers
         st = wl.synthetic_state(dev)
         self.errs, self.m, self.v, self.werr = st["errs"], st["m"], st["v"], st["werr"]

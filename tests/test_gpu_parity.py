@@ -699,3 +699,69 @@ def test_identity_quantizers_on_device(variant, idg, idx):
         with pytest.raises(QAdamError):
             q.weight_quantize(1, x, werr, errs[0])
     q.close()
+
+
+# ------------------------------------------------ filtered scale pass (qadam_trust_error_buffers)
+@pytest.mark.parametrize("config,shrink,steps", [(2, 8, 12), (3, 4, 8), (4, 64, 6), (5, 16, 6)])
+def test_filtered_scale_pass_matches_the_oracle(config, shrink, steps):
+    """With qadam_trust_error_buffers the scale pass reads e only where |g| can still reach the
+    layer's maximum; every output must stay what the oracle computes (Gaussian, heavy-tailed and
+    adversarial gradients; the first step reads everything, the later ones are filtered)."""
+    wl = make_workload(config, shrink=shrink)
+    rep = run_workload_parity(wl, steps, fused=True, trust_errs=True, progress="filtered cfg%d" % config)
+    _say("filtered scale pass, config %d/%d: %s" % (config, shrink, rep.line()))
+    assert rep.ok() and rep.float_not_bit_exact == 0
+
+
+@pytest.mark.parametrize("k_g,rounding", [(2, 0), (0, 0), (1, 1), (6, 0)])
+def test_filtered_scale_pass_equals_the_full_one(k_g, rounding):
+    """Same inputs through a handle with the option and one without, on ragged and unaligned
+    layers with gradients whose size changes from step to step (so the lower bound from the sample
+    and the bound on e are of different orders): bit-identical state after every step."""
+    gcfg, _ = configs(k_g=k_g, k_x=6, rounding=rounding, seed=3)
+    sizes = RAGGED + [1 << 19, 300001, 70000]
+    seg_off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    P, N = int(seg_off[-1]), 3
+    qa, qb = QAdam(gcfg, seg_off, N), QAdam(gcfg, seg_off, N)
+    qa.trust_error_buffers(2)
+    gen = torch.Generator().manual_seed(41 + k_g)
+    x0 = torch.randn(P, generator=gen) * 0.02
+    a, b = DeviceState(qa, x0), DeviceState(qb, x0)
+    amp = [1e-2, 1e-2, 1e-4, 1e-4, 1.0, 1e-3, 0.0, 1e-2, 1e-2]        # shrinking, growing, all-zero gradients
+    for t, scale in enumerate(amp, start=1):
+        for i in range(N):
+            g = torch.randn(P, generator=gen) * scale
+            if t == 5:
+                g[torch.rand(P, generator=gen) < 1e-4] = 50.0            # sparse outliers
+            a.grads[i].copy_(g); b.grads[i].copy_(g)
+        a.step_fused(t, 1e-3, 0.999)
+        b.step_fused(t, 1e-3, 0.999)
+        torch.cuda.synchronize()
+        for name in ("x", "m", "v", "werr", "wcodes"):
+            assert torch.equal(getattr(a, name), getattr(b, name)), (t, name)
+        for i in range(N):
+            assert torch.equal(a.scales[i], b.scales[i]), (t, i)
+            assert torch.equal(a.errs[i], b.errs[i]) and torch.equal(a.codes[i], b.codes[i]), (t, i)
+    assert qa.get_status() == 0 and qb.get_status() == 0
+    qa.close(); qb.close()
+
+
+def test_filtered_scale_pass_keeps_nonfinite_detection():
+    """A NaN or Inf gradient must still surface in the scale (and the status word) when the filter is on."""
+    gcfg, _ = configs(k_g=2, k_x=6)
+    seg_off = [0, 5000, 5000 + (1 << 19)]
+    P, N = seg_off[-1], 2
+    q = QAdam(gcfg, seg_off, N)
+    q.trust_error_buffers(2)
+    gen = torch.Generator().manual_seed(8)
+    ds = DeviceState(q, torch.randn(P, generator=gen) * 0.02)
+    for t in range(1, 4):
+        for i in range(N):
+            ds.grads[i].copy_(torch.randn(P, generator=gen) * 1e-2)
+        if t == 3:
+            ds.grads[1][5000 + 4096 * 70 + 17] = float("inf")        # in a tile that is not sampled
+        ds.step_fused(t, 1e-3, 0.999)
+        st = q.get_status()
+        assert (st != 0) == (t == 3), (t, st)
+    assert not torch.isfinite(ds.scales[1][1]) and torch.isfinite(ds.scales[0][1])
+    q.close()

@@ -214,6 +214,9 @@ def main():
                     help="full: the scale pass reads g and e of every element; filtered: "
                          "qadam_trust_error_buffers(1), it reads e only where |g| can still reach the layer's "
                          "maximum (same results; the error buffers are the library's between steps)")
+    ap.add_argument("--no-full-comparison", action="store_true",
+                    help="with the filtered scale pass: do not time the same steps again with the full one "
+                         "(for profiles of one mode)")
     ap.add_argument("--k-g", type=int, default=None,
                     help="override the workload's gradient grid (0: 2-bit codes, 1-2: 3-bit, 3-6: 4-bit, "
                          "-1: no gradient quantization)")
@@ -313,7 +316,7 @@ def main():
     res = timed_steps(1, args.warmup, args.steps)
     step_ms, scale_ms, main_ms = ([r[k] for r in res] for k in range(3))
     full_pass = None
-    if filtered:
+    if filtered and not args.no_full_comparison:
         # the same steps once more with the option off (every element's g and e read for the scales)
         q.trust_error_buffers(False)
         res_full = timed_steps(1 + args.warmup + args.steps, 1, args.steps)

@@ -186,7 +186,7 @@ int qadam_step_fused_w(qadam_handle_t h, int64_t step, float lr, float beta2,
 int qadam_weight_dequantize(qadam_handle_t h, const void* wcodes_dev, float* xhat_dev, void* stream);
 int qadam_weight_dequantize_f16(qadam_handle_t h, const void* wcodes_dev, void* xhat_dev, void* stream);
 
-/* Opt-in: let qadam_step_fused skip most of the first read of the error buffers.
+/* Opt-in: let qadam_step_fused and qadam_worker_quantize skip most of the first read of the error buffers.
  * The per-layer scale ||g_i + e_i||_inf normally costs one full read of g_i and e_i before the main pass.
  * The quantizer bounds the residual it leaves (|e| <= s/4 per element for k_g >= 1 with nearest rounding,
  * s/2 for the ternary grid, twice that with stochastic rounding), so when e_i is exactly what the previous

@@ -342,7 +342,10 @@ int qadam_worker_quantize(qadam_handle_t h, int32_t worker, int64_t step, const 
     W.codes[worker] = static_cast<uint32_t*>(codes_dev); W.scales[worker] = scales_dev;
     const StepScalars S = make_scalars(h, step, 0.0f, 0.0f);
     const Launch L = make_launch(h, stream);
-    QADAM_HIP(launch_amax(L, S, W, worker, 1));
+    const bool filtered = h->bound_valid[worker] &&
+                          (h->trust_errs == 2 || (h->trust_errs == 1 && h->num_tiles >= 4096));
+    if (filtered) QADAM_HIP(launch_amax_filtered(L, S, W, worker, 1));
+    else QADAM_HIP(launch_amax(L, S, W, worker, 1));
     QADAM_HIP(launch_reduce_scales(L, S, W, worker, 1));
     QADAM_HIP(launch_worker_quantize(L, S, W, worker));
     h->bound_valid[worker] = true;

@@ -746,6 +746,36 @@ def test_filtered_scale_pass_equals_the_full_one(k_g, rounding):
     qa.close(); qb.close()
 
 
+def test_filtered_scale_pass_in_the_separate_calls():
+    """qadam_worker_quantize with the option on (per-worker record of the bounds), mixed with whole-step
+    calls on the same handle: same bits as a handle without the option."""
+    gcfg, _ = configs(k_g=2, k_x=6)
+    sizes = RAGGED + [1 << 19, 123457]
+    seg_off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    P, N = int(seg_off[-1]), 3
+    qa, qb = QAdam(gcfg, seg_off, N), QAdam(gcfg, seg_off, N)
+    qa.trust_error_buffers(2)
+    gen = torch.Generator().manual_seed(77)
+    x0 = torch.randn(P, generator=gen) * 0.02
+    a, b = DeviceState(qa, x0), DeviceState(qb, x0)
+    for t in range(1, 7):
+        for i in range(N):
+            g = torch.randn(P, generator=gen) * (1e-2 if t != 4 else 1e-5)
+            a.grads[i].copy_(g); b.grads[i].copy_(g)
+        if t % 3 == 0:
+            a.step_fused(t, 1e-3, 0.999)
+        else:
+            a.step_unfused(t, 1e-3, 0.999)
+        b.step_fused(t, 1e-3, 0.999)
+        torch.cuda.synchronize()
+        for name in ("x", "m", "v", "werr", "wcodes"):
+            assert torch.equal(getattr(a, name), getattr(b, name)), (t, name)
+        for i in range(N):
+            assert torch.equal(a.scales[i], b.scales[i]) and torch.equal(a.errs[i], b.errs[i]), (t, i)
+            assert torch.equal(a.codes[i], b.codes[i]), (t, i)
+    qa.close(); qb.close()
+
+
 def test_filtered_scale_pass_keeps_nonfinite_detection():
     """A NaN or Inf gradient must still surface in the scale (and the status word) when the filter is on."""
     gcfg, _ = configs(k_g=2, k_x=6)

@@ -145,6 +145,23 @@ int check_ptr(const void* p, const char* name, bool required = true)
         if (rc_ != QADAM_OK) return rc_;  \
     } while (0)
 
+// Record of whether d_err_bound describes the error buffers: cleared for the workers a call is about
+// to rewrite, set again only when every launch of the call was accepted (a call that fails half way
+// leaves the record cleared, so the next step reads everything).
+struct BoundRecord {
+    qadam_ctx* h;
+    int first, num;
+    bool complete;
+    BoundRecord(qadam_ctx* h_, int first_, int num_) : h(h_), first(first_), num(num_), complete(false)
+    {
+        for (int i = first; i < first + num; ++i) h->bound_valid[i] = false;
+    }
+    ~BoundRecord()
+    {
+        for (int i = first; i < first + num; ++i) h->bound_valid[i] = complete;
+    }
+};
+
 bool identity_g(const qadam_ctx* h) { return h->cfg.k_g == QADAM_IDENTITY; }
 bool identity_x(const qadam_ctx* h) { return h->cfg.k_x == QADAM_IDENTITY; }
 
@@ -344,11 +361,12 @@ int qadam_worker_quantize(qadam_handle_t h, int32_t worker, int64_t step, const 
     const Launch L = make_launch(h, stream);
     const bool filtered = h->bound_valid[worker] &&
                           (h->trust_errs == 2 || (h->trust_errs == 1 && h->num_tiles >= 4096));
+    BoundRecord record(h, worker, 1);
     if (filtered) QADAM_HIP(launch_amax_filtered(L, S, W, worker, 1));
     else QADAM_HIP(launch_amax(L, S, W, worker, 1));
     QADAM_HIP(launch_reduce_scales(L, S, W, worker, 1));
     QADAM_HIP(launch_worker_quantize(L, S, W, worker));
-    h->bound_valid[worker] = true;
+    record.complete = true;
     return QADAM_OK;
 }
 
@@ -432,19 +450,23 @@ int qadam_step_fused(qadam_handle_t h, int64_t step, float lr, float beta2, cons
     const StepScalars S = make_scalars(h, step, lr, beta2);
     const Launch L = make_launch(h, stream);
     if (h->profile) QADAM_HIP(hipEventRecord(h->ev[0], L.stream));
-    if (!idg) {
+    if (idg) {
+        // the error buffers are not touched: whatever is recorded about them stays true
+        if (h->profile) QADAM_HIP(hipEventRecord(h->ev[1], L.stream));
+        QADAM_HIP(launch_plain_messages(L, S, W, sp, false));
+    } else {
         // the filtered pass costs two more (small) launches: only worth it beyond a few million worker-elements
         bool filtered = h->trust_errs == 2 ||
                         (h->trust_errs == 1 && (int64_t)h->num_tiles * h->num_workers >= 4096);
         for (int i = 0; i < h->num_workers; ++i) filtered = filtered && h->bound_valid[i];
+        BoundRecord record(h, 0, h->num_workers);
         if (filtered) QADAM_HIP(launch_amax_filtered(L, S, W, 0, h->num_workers));
         else QADAM_HIP(launch_amax(L, S, W, 0, h->num_workers));
         QADAM_HIP(launch_reduce_scales(L, S, W, 0, h->num_workers));
-        for (int i = 0; i < h->num_workers; ++i) h->bound_valid[i] = true;
+        if (h->profile) QADAM_HIP(hipEventRecord(h->ev[1], L.stream));
+        QADAM_HIP(launch_fused(L, S, W, sp));
+        record.complete = true;
     }
-    if (h->profile) QADAM_HIP(hipEventRecord(h->ev[1], L.stream));
-    if (idg) QADAM_HIP(launch_plain_messages(L, S, W, sp, false));
-    else QADAM_HIP(launch_fused(L, S, W, sp));
     if (h->profile) {
         QADAM_HIP(hipEventRecord(h->ev[2], L.stream));
         h->profile_valid = true;
@@ -474,12 +496,13 @@ int qadam_worker_step_w(qadam_handle_t h, int32_t worker, int64_t step, float lr
     const StepScalars S = make_scalars(h, step, lr, beta2);
     const Launch L = make_launch(h, stream);
     // pass 1: local moments, p = alpha m / sqrt(v + eps) + e parked in the error buffer, tile maxima
+    BoundRecord record(h, worker, 1);
     QADAM_HIP(launch_worker_moments_w(L, S, W, worker, 1));
     QADAM_HIP(launch_reduce_scales(L, S, W, worker, 1));
-    h->bound_valid[worker] = true;
     // pass 2: quantize the parked p
     W.grad[worker] = nullptr;
     QADAM_HIP(launch_worker_quantize(L, S, W, worker));
+    record.complete = true;
     return QADAM_OK;
 }
 
@@ -509,13 +532,14 @@ int qadam_step_fused_w(qadam_handle_t h, int64_t step, float lr, float beta2, co
     const Launch L = make_launch(h, stream);
     if (h->profile) QADAM_HIP(hipEventRecord(h->ev[0], L.stream));
     // pass 1 (all workers): local moments, p parked in the error buffers, tile maxima; then scales
+    BoundRecord record(h, 0, h->num_workers);
     QADAM_HIP(launch_worker_moments_w(L, S, W, 0, h->num_workers));
     if (!idg) QADAM_HIP(launch_reduce_scales(L, S, W, 0, h->num_workers));
-    for (int i = 0; i < h->num_workers; ++i) h->bound_valid[i] = !idg;
     if (h->profile) QADAM_HIP(hipEventRecord(h->ev[1], L.stream));
     // pass 2: quantize every worker's parked p, subtract the mean message, Q_x
     if (idg) QADAM_HIP(launch_plain_messages(L, S, W, sp, true));
     else QADAM_HIP(launch_fused_w(L, S, W, sp));
+    record.complete = !idg;     // with the identity quantizer no scale, hence no bound, was produced
     if (h->profile) {
         QADAM_HIP(hipEventRecord(h->ev[2], L.stream));
         h->profile_valid = true;

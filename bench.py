@@ -135,11 +135,13 @@ def measure_ceilings(dev):
 
     inplace = best(lambda: t.mul_(1.0))
     copy = best(lambda: t[half:].copy_(t[:half]))
+    fill = best(lambda: t.fill_(1.0))
     del t
     torch.cuda.empty_cache()
     return {"inplace_update_GBs": round(2 * 4 * n / inplace / 1e6, 1),
             "device_copy_GBs": round(2 * 4 * half / copy / 1e6, 1),
-            "note": "torch x.mul_(1.0) over 6 GiB (reads + writes counted) and a 3 GiB -> 3 GiB copy"}
+            "fill_GBs": round(4 * n / fill / 1e6, 1),
+            "note": "torch x.mul_(1.0) over 6 GiB (reads + writes counted), a 3 GiB -> 3 GiB copy, x.fill_(1.0) over 6 GiB"}
 
 
 def bench_calls(args, wl, q, grads, errs, codes, scales, x, m, v, werr, wcodes, code_bits, wcode_bytes):

@@ -491,7 +491,8 @@ __global__ void __launch_bounds__(kBlockThreads) k_reduce_scales(ScaleArgs A)
         A.inv_scales[(size_t)w * A.num_segments + l] = ok ? 1.0f / s : 0.0f;
         // what the residual p - Q_g(p) of this step can reach (a non-finite scale gives a non-finite
         // bound, which switches the next step's filter off)
-        A.err_bound[(size_t)w * A.num_segments + l] = s * A.bound_factor;
+        // bound on the next |e|; the added 2^-140 covers scales so small that s * level itself is rounded
+        A.err_bound[(size_t)w * A.num_segments + l] = s * A.bound_factor + 0x1p-140f;
     }
 }
 

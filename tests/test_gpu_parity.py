@@ -727,7 +727,8 @@ def test_filtered_scale_pass_equals_the_full_one(k_g, rounding):
     gen = torch.Generator().manual_seed(41 + k_g)
     x0 = torch.randn(P, generator=gen) * 0.02
     a, b = DeviceState(qa, x0), DeviceState(qb, x0)
-    amp = [1e-2, 1e-2, 1e-4, 1e-4, 1.0, 1e-3, 0.0, 1e-2, 1e-2]        # shrinking, growing, all-zero gradients
+    # shrinking, growing and all-zero gradients, then layers that live entirely among the subnormals
+    amp = [1e-2, 1e-2, 1e-4, 1e-4, 1.0, 1e-3, 0.0, 1e-2, 1e-2, 1e-30, 1e-39, 1e-39, 1e-43, 1e-43, 1e-44, 1e-2]
     for t, scale in enumerate(amp, start=1):
         for i in range(N):
             g = torch.randn(P, generator=gen) * scale

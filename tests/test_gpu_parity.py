@@ -77,13 +77,14 @@ def test_config5_gpt13b_shrunk():
 RAGGED = [1, 3, 31, 33, 0, 255, 257, 4095, 4097, 5000, 0, 64, 8192, 2, 12289, 7]
 
 
-def _custom(sizes, N, steps, seed=1, cfgkw=None, fused=True, scale=1e-2, weight_quant=True, gsel=None):
+def _custom(sizes, N, steps, seed=1, cfgkw=None, fused=True, scale=1e-2, weight_quant=True, gsel=None, trust=0):
     cfgkw = cfgkw or {}
     gcfg, ocfg = configs(**cfgkw)
     seg_off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
     P = int(seg_off[-1])
     rng = np.random.default_rng(seed)
     q = QAdam(gcfg, seg_off, N)
+    q.trust_error_buffers(trust)
     x0 = (rng.standard_normal(P) * 0.02).astype(np.float32)
     ds = DeviceState(q, torch.from_numpy(x0))
     hs = HostState(P, N, x0)
@@ -796,3 +797,26 @@ def test_filtered_scale_pass_keeps_nonfinite_detection():
         assert (st != 0) == (t == 3), (t, st)
     assert not torch.isfinite(ds.scales[1][1]) and torch.isfinite(ds.scales[0][1])
     q.close()
+
+
+@pytest.mark.parametrize("k_g,trust", [(2, 0), (2, 2), (0, 2), (5, 2)])
+def test_gradients_of_random_bit_patterns(k_g, trust):
+    """Gradients whose sign, exponent and significand are drawn independently (magnitudes from
+    2^-140, far inside the subnormals, to 2^15, over 150 binades in one layer), in many short ragged
+    layers: the scale, the fast quotient with its fallback and the residual must follow the oracle
+    bit for bit, with the full and with the filtered scale pass."""
+    def bits(t, grads):
+        rng = np.random.default_rng(1000 * k_g + t)
+        out = []
+        for g in grads:
+            n = g.size
+            expo = rng.integers(-140, 16, n)
+            frac = 1.0 + rng.integers(0, 1 << 23, n) * 2.0 ** -23
+            val = np.ldexp(frac, expo) * rng.choice([-1.0, 1.0], n)
+            val[rng.random(n) < 0.02] = 0.0
+            out.append(val.astype(np.float32))
+        return out
+    sizes = [int(v) for v in np.random.default_rng(5).integers(1, 3000, 40)] + [0, 50000]
+    rep, st = _custom(sizes, 3, 4, cfgkw=dict(k_g=k_g), gsel=bits, seed=90 + k_g, trust=trust)
+    _say("random bit patterns k_g=%d trust=%d: %s" % (k_g, trust, rep.line()))
+    assert rep.ok() and st == 0 and rep.float_not_bit_exact == 0

@@ -216,6 +216,9 @@ def main():
                     help="full: the scale pass reads g and e of every element; filtered: "
                          "qadam_trust_error_buffers(1), it reads e only where |g| can still reach the layer's "
                          "maximum (same results; the error buffers are the library's between steps)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture the step in a HIP graph after the warm-up and time replays of it (pays on "
+                         "launch-bound workloads such as config 1; kernels are then not timed one by one)")
     ap.add_argument("--no-full-comparison", action="store_true",
                     help="with the filtered scale pass: do not time the same steps again with the full one "
                          "(for profiles of one mode)")
@@ -256,7 +259,7 @@ def main():
     cfg = QAdamConfig(k_g=wl.k_g, k_x=wl.k_x, rounding=args.rounding, weight_ef=weight_ef, beta1=wl.beta1,
                       eps=wl.eps)
     q = QAdam(cfg, wl.seg_offsets, N)
-    q.profile_enable(True)
+    q.profile_enable(not args.graph)
     if args.scale_pass == "filtered":
         q.trust_error_buffers(True)
     code_bits = q.grad_code_bytes() * 8.0 / P
@@ -293,21 +296,34 @@ def main():
             sys.exit("bench.py: --path calls is for variant S")
         return bench_calls(args, wl, q, grads, errs, codes, scales, x, m, v, werr, wcodes, code_bits, wcode_bytes)
 
+    def step_call(t):
+        if args.variant == "s":
+            q.step_fused(t, wl.lr, wl.beta2, grads, errs, codes, scales, x, m, v, werr, wcodes)
+        else:
+            q.step_fused_w(t, wl.lr, wl.beta2, grads, mw, vw, errs, codes, scales, x, werr, wcodes)
+
     def timed_steps(first, warmup, steps):
         """`warmup` untimed then `steps` timed steps; each timed between two device synchronisations,
         with the step's gradients already resident.  Returns per-step (wall, scale pass, main pass) ms."""
         out = []
+        graph = None
         for t in range(first, first + warmup + steps):
             wl.fill_gradients(t, grads)        # untimed: inputs are resident before the clock starts
             torch.cuda.synchronize()
+            if args.graph and graph is None and t >= first + warmup:
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph):  # capture only records: nothing runs, no state changes
+                    step_call(t)
+                torch.cuda.synchronize()
             t0 = time.perf_counter()
-            if args.variant == "s":
-                q.step_fused(t, wl.lr, wl.beta2, grads, errs, codes, scales, x, m, v, werr, wcodes)
+            if graph is not None:
+                graph.replay()
             else:
-                q.step_fused_w(t, wl.lr, wl.beta2, grads, mw, vw, errs, codes, scales, x, werr, wcodes)
+                step_call(t)
             torch.cuda.synchronize()
             dt = (time.perf_counter() - t0) * 1e3
-            a, b = q.profile_read()
+            # per-pass HIP events are not recorded into a graph: split the wall time evenly as a placeholder
+            a, b = (dt / 2, dt / 2) if args.graph else q.profile_read()
             if t >= first + warmup:
                 out.append((dt, a, b))
         return out
@@ -363,197 +379,12 @@ def main():
                                    "achieved": gbs(a_scale, scale_avg)},
                     "whole_step_GBs": gbs(a_main + a_scale, ms_per_step)}
 
-    out = {
-        "metric": "parameters updated/sec (full QAdam-EF step)",
-        "value": P / (ms_per_step * 1e-3), "unit": "params/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "config %d: %s, %d logical workers, %d parameters, the step as %d x "
-                               "qadam_worker_quantize + qadam_server_step + qadam_weight_quantize"
-                               % (wl.config, wl.name, N, P, N),
-                   "status_word": q.get_status()},
-        "roofline": {"bound": "hbm", "kernel": "qadam_worker_quantize x %d (k_amax + k_worker_quantize per worker)" % N,
-                     "achieved": gbs(a_worker, w_ms), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(gbs(a_worker, w_ms) / HBM_PEAK_GBS, 4), "traffic": None,
-                     "algorithmic_bytes_per_param": a_worker, "avg_launch_ms": round(w_ms, 4),
-                     "server_step": {"algorithmic_bytes_per_param": a_server, "avg_launch_ms": round(s_ms, 4),
-                                     "achieved": gbs(a_server, s_ms)},
-                     "weight_quantize": {"algorithmic_bytes_per_param": a_weight, "avg_launch_ms": round(x_ms, 4),
-                                         "achieved": gbs(a_weight, x_ms)}},
-    }
-    print(json.dumps(out), flush=True)
-
-
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", type=int, default=5, help="workload 1..5 (default: the 1.3B headline)")
-    ap.add_argument("--shrink", type=int, default=1, help="divide model dims (debugging only)")
-    ap.add_argument("--variant", choices=["s", "w"], default="s",
-                    help="s: workers quantize g+e, server owns the moments (the headline path); "
-                         "w: Algorithms 2-3 as printed, workers own the moments (qadam_step_fused_w)")
-    ap.add_argument("--path", choices=["fused", "calls"], default="fused",
-                    help="fused: qadam_step_fused (the headline); calls: the same step as N x "
-                         "qadam_worker_quantize + qadam_server_step + qadam_weight_quantize (variant S only)")
-    ap.add_argument("--rounding", type=int, choices=[0, 1], default=0,
-                    help="0: nearest (the paper's quantizers, the headline); 1: unbiased stochastic rounding "
-                         "driven by Philox4x32-10")
-    ap.add_argument("--scale-pass", choices=["full", "filtered"], default="filtered",
-                    help="full: the scale pass reads g and e of every element; filtered: "
-                         "qadam_trust_error_buffers(1), it reads e only where |g| can still reach the layer's "
-                         "maximum (same results; the error buffers are the library's between steps)")
-    ap.add_argument("--no-full-comparison", action="store_true",
-                    help="with the filtered scale pass: do not time the same steps again with the full one "
-                         "(for profiles of one mode)")
-    ap.add_argument("--k-g", type=int, default=None,
-                    help="override the workload's gradient grid (0: 2-bit codes, 1-2: 3-bit, 3-6: 4-bit, "
-                         "-1: no gradient quantization)")
-    ap.add_argument("--k-x", type=int, default=None,
-                    help="override the workload's weight grid (0-6: int8, 7-14: int16, -1: no weight quantization)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--alloc-cycles", type=int, default=5,
-                    help="allocate and free the working set this many times before the real allocation "
-                         "(0: measure on whatever placement a fresh process gets; see condition_allocator)")
-    ap.add_argument("--ceilings", action="store_true",
-                    help="also time plain torch streams over 6 GiB (an in-place update: half reads, half "
-                         "writes; a device copy) and add them to the JSON line as memory_system: what "
-                         "this box delivers to the simplest kernels, next to the 8 TB/s peak")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run one plain 4 GiB device copy (a kernel of known traffic, to scale "
-                         "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.exit("bench.py: this build runs on ONE GPU (logical workers are in-memory shards of one "
-                 "device); --gpus %d is not supported" % args.gpus)
-
-    import torch
-    from paper_2004_14180_amd import QAdam, QAdamConfig
-    from paper_2004_14180_amd.workloads import make_workload
-
-    dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-    wl = make_workload(args.config, shrink=args.shrink)
-    if args.k_g is not None:
-        wl.k_g = args.k_g
-    if args.k_x is not None:
-        wl.k_x = args.k_x
-    P, N = wl.num_params, wl.num_workers
-    weight_ef = 1
-    cfg = QAdamConfig(k_g=wl.k_g, k_x=wl.k_x, rounding=args.rounding, weight_ef=weight_ef, beta1=wl.beta1,
-                      eps=wl.eps)
-    q = QAdam(cfg, wl.seg_offsets, N)
-    q.profile_enable(True)
-    if args.scale_pass == "filtered":
-        q.trust_error_buffers(True)
-    code_bits = q.grad_code_bytes() * 8.0 / P
-    wcode_bytes = q.weight_code_bytes() / P
-
-    n_f32 = 4 + 2 * N + (2 * N if args.variant == "w" else 0)
-    working_set = [4 * P] * n_f32 + [q.grad_code_bytes()] * N + [q.weight_code_bytes()]
-    if args.alloc_cycles > 0:
-        condition_allocator(working_set, args.alloc_cycles, dev)
-
-    z = lambda: torch.zeros(P, dtype=torch.float32, device=dev)
-    x = wl.init_weights(dev)
-    m, v, werr = z(), z(), z()
-    errs = [z() for _ in range(N)]
-    grads = [torch.empty(P, dtype=torch.float32, device=dev) for _ in range(N)]
-    if args.variant == "w":
-        mw = [z() for _ in range(N)]
-        vw = [z() for _ in range(N)]
-    codes = [torch.empty(max(q.grad_code_bytes() // 4, 4), dtype=torch.int32, device=dev) for _ in range(N)]
-    scales = [torch.empty(q.num_segments, dtype=torch.float32, device=dev) for _ in range(N)]
-    wcodes = torch.empty(P, dtype=torch.int8 if wl.k_x <= 6 else torch.int16, device=dev)
-
-    if args.copy_calibration:
-        src = torch.ones(1 << 30, dtype=torch.float32, device=dev)
-        dst = torch.empty_like(src)
-        dst.copy_(src)                      # reads 4 GiB, writes 4 GiB
-        torch.cuda.synchronize()
-        del src, dst
-
-    memory_system = measure_ceilings(dev) if args.ceilings else None
-
-    if args.path == "calls":
-        if args.variant != "s":
-            sys.exit("bench.py: --path calls is for variant S")
-        return bench_calls(args, wl, q, grads, errs, codes, scales, x, m, v, werr, wcodes, code_bits, wcode_bytes)
-
-    def timed_steps(first, warmup, steps):
-        """`warmup` untimed then `steps` timed steps; each timed between two device synchronisations,
-        with the step's gradients already resident.  Returns per-step (wall, scale pass, main pass) ms."""
-        out = []
-        for t in range(first, first + warmup + steps):
-            wl.fill_gradients(t, grads)        # untimed: inputs are resident before the clock starts
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            if args.variant == "s":
-                q.step_fused(t, wl.lr, wl.beta2, grads, errs, codes, scales, x, m, v, werr, wcodes)
-            else:
-                q.step_fused_w(t, wl.lr, wl.beta2, grads, mw, vw, errs, codes, scales, x, werr, wcodes)
-            torch.cuda.synchronize()
-            dt = (time.perf_counter() - t0) * 1e3
-            a, b = q.profile_read()
-            if t >= first + warmup:
-                out.append((dt, a, b))
-        return out
-
-    # the library applies the filter from about four million worker-elements on (4096 tiles of 4096)
-    tiles = sum((n + 4095) // 4096 for n in wl.sizes)
-    filtered = args.scale_pass == "filtered" and args.variant == "s" and wl.k_g >= 0 and tiles * N >= 4096
-    res = timed_steps(1, args.warmup, args.steps)
-    step_ms, scale_ms, main_ms = ([r[k] for r in res] for k in range(3))
-    full_pass = None
-    if filtered and not args.no_full_comparison:
-        # the same steps once more with the option off (every element's g and e read for the scales)
-        q.trust_error_buffers(False)
-        res_full = timed_steps(1 + args.warmup + args.steps, 1, args.steps)
-        full_ms = sum(r[0] for r in res_full) / len(res_full)
-        full_pass = {"ms_per_step": round(full_ms, 4), "value": P / (full_ms * 1e-3),
-                     "scale_pass_ms": round(sum(r[1] for r in res_full) / len(res_full), 4),
-                     "main_pass_ms": round(sum(r[2] for r in res_full) / len(res_full), 4)}
-    if os.environ.get("QADAM_BENCH_VERBOSE"):
-        print("per-step main ms:", [round(v_, 2) for v_ in main_ms], file=sys.stderr)
-        print("per-step scale ms:", [round(v_, 2) for v_ in scale_ms], file=sys.stderr)
-    status = q.get_status()
-    total_ms = sum(step_ms)
-    ms_per_step = total_ms / len(step_ms)
-    main_avg = sum(main_ms) / len(main_ms)
-    scale_avg = sum(scale_ms) / len(scale_ms)
-
-    if args.variant == "w":
-        # first pass (dominant): per worker read g, m_i, v_i, e_i and write m_i, v_i, p = 28 B;
-        # second pass: per worker read p, write e and the code; server read/write x and e^x, weight code
-        a_first = 28.0 * N
-        a_second = N * (8.0 + code_bits / 8.0) + 8.0 + (8.0 if weight_ef else 4.0) + wcode_bytes
-        achieved = a_first * P / (scale_avg * 1e-3) / 1e9
-        roofline = {"bound": "hbm", "kernel": "k_moments_w (first pass of qadam_step_fused_w)",
-                    "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                    "algorithmic_bytes_per_param": a_first, "avg_launch_ms": round(scale_avg, 4),
-                    "second_pass": {"algorithmic_bytes_per_param": a_second, "avg_launch_ms": round(main_avg, 4),
-                                    "achieved": round(a_second * P / (main_avg * 1e-3) / 1e9, 1)},
-                    "whole_step_GBs": round((a_first + a_second) * P / (ms_per_step * 1e-3) / 1e9, 1)}
-    a_main = algorithmic_bytes_per_param(N, code_bits, wcode_bytes, weight_ef)
-    # scale pass: g and e of every worker; filtered: g, plus e of the few elements that can be the maximum
-    a_scale = (4.0 if filtered else 8.0) * N if code_bits else 0.0
-    achieved = a_main * P / (main_avg * 1e-3) / 1e9
-    roofline_s = {"bound": "hbm", "kernel": "k_fused (main pass of qadam_step_fused)",
-                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get(args.config)
-                if args.shrink == 1 and args.k_g is None and args.k_x is None and args.rounding == 0 else None,
-                "algorithmic_bytes_per_param": a_main,
-                "avg_launch_ms": round(main_avg, 4),
-                "scale_pass": {"mode": "filtered" if filtered else "full", "algorithmic_bytes_per_param": a_scale,
-                               "avg_launch_ms": round(scale_avg, 4),
-                               "achieved": round(a_scale * P / (max(scale_avg, 1e-6) * 1e-3) / 1e9, 1)},
-                "whole_step_GBs": round((a_main + a_scale) * P / (ms_per_step * 1e-3) / 1e9, 1)}
-    if args.variant == "s":
-        roofline = roofline_s
-
+    if args.graph:
+        # the passes are not timed one by one inside a graph: report the whole step against the roofline
+        whole = roofline["whole_step_GBs"]
+        roofline = {"bound": "hbm", "kernel": "whole step (HIP graph replay)", "achieved": whole,
+                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(whole / HBM_PEAK_GBS, 4), "traffic": None,
+                    "avg_launch_ms": round(ms_per_step, 4)}
     out = {
         "metric": "parameters updated/sec (full QAdam-EF step)",
         "value": P / (ms_per_step * 1e-3),
@@ -571,6 +402,7 @@ def main():
                    "worker_elements_per_s": N * P / (ms_per_step * 1e-3),
                    "resident_bytes": sum(working_set),
                    "allocator_conditioning_cycles": args.alloc_cycles,
+                   "hip_graph_replay": bool(args.graph),
                    "scale_pass": "filtered: exact scales, e read only where |g| can reach the layer maximum "
                                  "(qadam_trust_error_buffers)" if filtered else "full: g and e of every element",
                    "same_steps_with_full_scale_pass": full_pass,

@@ -171,7 +171,8 @@ def bench_calls(args, wl, q, grads, errs, codes, scales, x, m, v, werr, wcodes, 
             part_ms.append((e0.elapsed_time(e1), e1.elapsed_time(e2), e2.elapsed_time(e3)))
     ms_per_step = sum(step_ms) / len(step_ms)
     w_ms, s_ms, x_ms = (sum(p[k] for p in part_ms) / len(part_ms) for k in range(3))
-    a_worker = N * (8.0 + 12.0 + code_bits / 8.0)     # scale read of g, e; then g, e in, e and code out
+    filt = args.scale_pass == "filtered"               # the scale read is g only (plus the few e that matter)
+    a_worker = N * ((4.0 if filt else 8.0) + 12.0 + code_bits / 8.0)   # scale read; then g, e in, e and code out
     a_server = N * code_bits / 8.0 + 24.0             # codes in; m, v, x in and out
     a_weight = 4.0 + 8.0 + wcode_bytes                # x in; e^x in and out; weight code out
     gbs = lambda a, ms: round(a * P / (ms * 1e-3) / 1e9, 1)

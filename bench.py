@@ -45,7 +45,6 @@ def algorithmic_bytes_per_param(N, code_bits, wcode_bytes, weight_ef):
 def cpu_baseline(wl, sample_layers, seconds_hint=20.0):
     """The oracle as it stands, one thread, on a bounded sample of the workload's layers; then the same
     calls once more spread over the host's cores (layers are independent), as a second figure."""
-    import numpy as np
     import torch
     from concurrent.futures import ThreadPoolExecutor
     from oracle import qadam_oracle as oracle

@@ -7,7 +7,6 @@ of the largest layers with the layer's scale taken from its definition, numpy's 
 fp32.  Inputs are synthetic and seeded (including a synthetic mid-training state, so that one step
 exercises every buffer); nothing fed to the oracle comes from the GPU library.
 """
-import os
 from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np

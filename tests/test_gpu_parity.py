@@ -8,7 +8,7 @@ import torch
 
 from oracle import qadam_oracle as oracle
 from paper_2004_14180_amd import QAdam, QAdamConfig, QAdamError
-from paper_2004_14180_amd.workloads import Workload, make_workload
+from paper_2004_14180_amd.workloads import make_workload
 
 from parity_util import (DeviceState, HostState, Report, compare_step, configs, oracle_step_layers,
                          run_workload_parity)

@@ -1,11 +1,9 @@
 """The pins must bite: plant plausible mistakes in copies of the oracle's C source (on the CPU, in
 a temporary directory) and check that every mutant is rejected by at least one of the pin tests.
 The real oracle is never modified."""
-import ctypes as C
 import importlib.util
 import os
 import shutil
-import subprocess
 import sys
 
 import pytest

@@ -3,7 +3,6 @@ binary32 values -- subnormals, huge magnitudes, signed zeros, repeated values, a
 must satisfy what Sec. 5.1 and Assumptions 2-3 of arXiv 2004.14180 fix for EVERY input, not only
 for the Gaussian-like vectors of the other tests."""
 import numpy as np
-import pytest
 from hypothesis import given, settings, HealthCheck
 from hypothesis import strategies as st
 from hypothesis.extra import numpy as hnp

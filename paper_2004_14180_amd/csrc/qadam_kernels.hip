@@ -17,6 +17,10 @@
 //     wavefronts, one plain store of the tile's maximum; a second small kernel reduces the tiles of
 //     each (worker, layer).  No atomics: thousands of workgroups hitting one freshly zeroed word
 //     at the start of every layer cost more than the whole pass;
+//   * when the error buffers are what the previous step wrote, |e| <= s/4 (half the widest gap of
+//     the grid), so an element whose |g| lies that far below a known lower bound of the scale
+//     cannot be the maximum: the filtered scale pass takes the exact maxima of every 64th tile as
+//     that lower bound and then reads g alone, and e only for the few elements that can matter;
 //   * codes are stored as bit planes of 32-element groups; a lane's four codes are combined with
 //     the other seven lanes of its group by three DPP OR steps per plane, so packing costs no
 //     LDS traffic and no scatter;

@@ -87,6 +87,8 @@ extern "C" {
 
 /* status word bits */
 #define QADAM_STATUS_NONFINITE_SCALE 1u   /* some ||g+e||_inf was NaN or Inf */
+#define QADAM_STATUS_ERR_BOUND_VIOLATED 2u /* qadam_trust_error_buffers(h, 3): an error buffer was not what the
+                                             previous step left (some |e| beyond the recorded bound) */
 
 typedef struct qadam_ctx* qadam_handle_t;
 
@@ -199,7 +201,10 @@ int qadam_weight_dequantize_f16(qadam_handle_t h, const void* wcodes_dev, void* 
  * function again, which makes the next step read everything).  The first step after qadam_init, or after
  * this call, always reads everything.  Violating the contract gives scales that are too small.
  * on = 1 uses the filtered pass only where it pays (it adds two small launches: from about four
- * million worker-elements on); on = 2 uses it always; on = 0 (the default) never. */
+ * million worker-elements on); on = 2 uses it always; on = 0 (the default) never.
+ * on = 3 is a bring-up aid: the scale pass reads everything as with 0, and in addition every error buffer is
+ * checked against the bound recorded by the previous step; a violation sets QADAM_STATUS_ERR_BOUND_VIOLATED
+ * in the status word.  An integration that runs clean with 3 honours the contract of 1 and 2. */
 int qadam_trust_error_buffers(qadam_handle_t h, int32_t on);
 
 /* Diagnostic: per-layer squared Euclidean norms  out[l] = sum_{j in layer l} (a_j + b_j)^2, with the sum

@@ -18,6 +18,7 @@ QADAM_OK, QADAM_EINVAL, QADAM_EALIGN, QADAM_ERANGE, QADAM_EHIP = 0, -1, -2, -3, 
 QADAM_MAX_WORKERS = 32
 QADAM_IDENTITY = -1          # k_g or k_x: that quantizer is the identity
 QADAM_STATUS_NONFINITE_SCALE = 1
+QADAM_STATUS_ERR_BOUND_VIOLATED = 2
 
 EXPORTS = [
     "qadam_init", "qadam_destroy", "qadam_grad_code_bytes", "qadam_weight_code_bytes",
@@ -230,7 +231,7 @@ class QAdam:
 
     def trust_error_buffers(self, on=1):
         """Opt in to the filtered scale pass (see include/qadam.h for the contract):
-        0 off, 1 where it pays, 2 always."""
+        0 off, 1 where it pays, 2 always, 3 full pass plus a check of the contract (status bit 2)."""
         self._check(self._lib.qadam_trust_error_buffers(self._h, int(on)))
 
     def profile_enable(self, on=True):

@@ -31,7 +31,7 @@ struct qadam_ctx {
     uint32_t* d_thr;            // [num_workers][num_segments]
     int32_t*  d_sample_tiles;   // indices of the sampled tiles
     int32_t   num_sample_tiles;
-    int       trust_errs;                       // qadam_trust_error_buffers: 0 off, 1 when it pays, 2 always
+    int       trust_errs;                       // qadam_trust_error_buffers: 0 off, 1 when it pays, 2 always, 3 verify
     bool      bound_valid[QADAM_MAX_WORKERS];   // d_err_bound row i describes what errs[i] now holds
     bool       profile;
     bool       profile_valid;
@@ -361,6 +361,7 @@ int qadam_worker_quantize(qadam_handle_t h, int32_t worker, int64_t step, const 
     const Launch L = make_launch(h, stream);
     const bool filtered = h->bound_valid[worker] &&
                           (h->trust_errs == 2 || (h->trust_errs == 1 && h->num_tiles >= 4096));
+    if (h->trust_errs == 3 && h->bound_valid[worker]) QADAM_HIP(launch_check_error_bounds(L, W, worker, 1));
     BoundRecord record(h, worker, 1);
     if (filtered) QADAM_HIP(launch_amax_filtered(L, S, W, worker, 1));
     else QADAM_HIP(launch_amax(L, S, W, worker, 1));
@@ -458,7 +459,10 @@ int qadam_step_fused(qadam_handle_t h, int64_t step, float lr, float beta2, cons
         // the filtered pass costs two more (small) launches: only worth it beyond a few million worker-elements
         bool filtered = h->trust_errs == 2 ||
                         (h->trust_errs == 1 && (int64_t)h->num_tiles * h->num_workers >= 4096);
-        for (int i = 0; i < h->num_workers; ++i) filtered = filtered && h->bound_valid[i];
+        bool all_recorded = true;
+        for (int i = 0; i < h->num_workers; ++i) all_recorded = all_recorded && h->bound_valid[i];
+        filtered = filtered && all_recorded;
+        if (h->trust_errs == 3 && all_recorded) QADAM_HIP(launch_check_error_bounds(L, W, 0, h->num_workers));
         BoundRecord record(h, 0, h->num_workers);
         if (filtered) QADAM_HIP(launch_amax_filtered(L, S, W, 0, h->num_workers));
         else QADAM_HIP(launch_amax(L, S, W, 0, h->num_workers));
@@ -575,7 +579,7 @@ int qadam_layer_sumsq(qadam_handle_t h, const float* a_dev, const float* b_dev, 
 int qadam_trust_error_buffers(qadam_handle_t h, int32_t on)
 {
     QADAM_CHECK(check_handle(h));
-    if (on < 0 || on > 2) return fail(QADAM_EINVAL, "on must be 0, 1 or 2");
+    if (on < 0 || on > 3) return fail(QADAM_EINVAL, "on must be 0, 1, 2 or 3");
     h->trust_errs = on;
     for (bool& b : h->bound_valid) b = false;     // the next step reads everything and starts the record
     return QADAM_OK;

@@ -86,6 +86,7 @@ struct Launch {
 hipError_t launch_amax(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker, int num);
 hipError_t launch_reduce_scales(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker, int num);
 hipError_t launch_amax_filtered(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker, int num);
+hipError_t launch_check_error_bounds(const Launch& L, const WorkerPtrs& W, int first_worker, int num);
 hipError_t launch_worker_quantize(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int worker);
 hipError_t launch_server_step(const Launch& L, const StepScalars& S, const WorkerPtrs& W, const ServerPtrs& sp);
 hipError_t launch_weight_quantize(const Launch& L, const StepScalars& S, const float* x, float* werr, void* wcodes);

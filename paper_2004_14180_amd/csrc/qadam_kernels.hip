@@ -406,6 +406,8 @@ struct AmaxArgs {
     const int32_t* tile_list;   // null: workgroup b takes tile b; else tile tile_list[b] (the sampled tiles)
     const uint32_t* thr;        // filtered pass only: [N][L] thresholds on |g| as bit patterns (0: read everything)
     int num_segments;
+    const float* err_bound;     // verification only: [N][L] bounds the error buffers must respect
+    uint32_t* status;
 };
 
 struct FusedArgs {
@@ -655,6 +657,28 @@ __global__ void __launch_bounds__(kBlockThreads) k_amax_filtered(AmaxArgs A)
     }
     const uint32_t bm = block_max(local);
     if (threadIdx.x == 0) A.tile_max[(size_t)w * A.num_tiles + ti] = bm;
+}
+
+// Verification of the contract behind the filtered pass (bring-up aid): every |e_j| must be within
+// the bound the previous step recorded for its layer.  grid: (tiles, workers); reads e only.
+__global__ void __launch_bounds__(kBlockThreads) k_check_error_bounds(AmaxArgs A)
+{
+    const int ti = blockIdx.x;
+    const Tile t = A.tiles[ti];
+    const int w = A.first_worker + blockIdx.y;
+    const float* e = A.err[w];
+    uint32_t local = 0;
+    for (int off = threadIdx.x; off < t.len; off += kBlockThreads) {
+        const uint32_t ab = f2u(e[t.start + off]) & 0x7fffffffu;
+        local = ab > local ? ab : local;
+    }
+    const uint32_t bm = block_max(local);
+    if (threadIdx.x == 0) {
+        const float bound = A.err_bound[(size_t)w * A.num_segments + t.seg];
+        // a NaN or Inf in e, or a magnitude beyond a finite bound, breaks the contract
+        const bool finite_bound = bound < __builtin_inff();
+        if (finite_bound && !(u2f(bm) <= bound)) atomicOr(A.status, QADAM_STATUS_ERR_BOUND_VIOLATED);
+    }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1204,6 +1228,16 @@ static void fill_amax_args(AmaxArgs& A, const Launch& L, const WorkerPtrs& W, in
     A.tile_max = L.tile_max;
     A.first_worker = first_worker;
     A.tile_list = nullptr; A.thr = L.thr; A.num_segments = L.num_segments;
+    A.err_bound = L.err_bound; A.status = L.status;
+}
+
+hipError_t launch_check_error_bounds(const Launch& L, const WorkerPtrs& W, int first_worker, int num)
+{
+    if (L.num_tiles == 0 || num == 0) return hipSuccess;
+    AmaxArgs A;
+    fill_amax_args(A, L, W, first_worker);
+    hipLaunchKernelGGL(k_check_error_bounds, dim3(L.num_tiles, num), dim3(kBlockThreads), 0, L.stream, A);
+    return hipGetLastError();
 }
 
 hipError_t launch_amax(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker, int num)

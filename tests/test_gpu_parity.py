@@ -820,3 +820,32 @@ def test_gradients_of_random_bit_patterns(k_g, trust):
     rep, st = _custom(sizes, 3, 4, cfgkw=dict(k_g=k_g), gsel=bits, seed=90 + k_g, trust=trust)
     _say("random bit patterns k_g=%d trust=%d: %s" % (k_g, trust, rep.line()))
     assert rep.ok() and st == 0 and rep.float_not_bit_exact == 0
+
+
+def test_contract_of_the_filtered_pass_can_be_verified():
+    """qadam_trust_error_buffers(h, 3): a loop that leaves the error buffers alone runs clean; one that
+    changes them between steps gets QADAM_STATUS_ERR_BOUND_VIOLATED (and still correct scales: this
+    mode reads everything)."""
+    from paper_2004_14180_amd.binding import QADAM_STATUS_ERR_BOUND_VIOLATED
+    gcfg, _ = configs(k_g=2, k_x=6)
+    seg_off = [0, 3000, 3000 + 70000]
+    P, N = seg_off[-1], 2
+    qa, qb = QAdam(gcfg, seg_off, N), QAdam(gcfg, seg_off, N)
+    qa.trust_error_buffers(3)
+    gen = torch.Generator().manual_seed(13)
+    x0 = torch.randn(P, generator=gen) * 0.02
+    a, b = DeviceState(qa, x0), DeviceState(qb, x0)
+    for t in range(1, 6):
+        for i in range(N):
+            g = torch.randn(P, generator=gen) * 1e-2
+            a.grads[i].copy_(g); b.grads[i].copy_(g)
+        if t == 4:                       # the caller meddles with one error buffer
+            a.errs[1].mul_(8.0); b.errs[1].mul_(8.0)
+        a.step_fused(t, 1e-3, 0.999)
+        b.step_fused(t, 1e-3, 0.999)
+        st = qa.get_status(clear=True)
+        assert st == (QADAM_STATUS_ERR_BOUND_VIOLATED if t == 4 else 0), (t, st)
+        for i in range(N):
+            assert torch.equal(a.scales[i], b.scales[i]) and torch.equal(a.errs[i], b.errs[i])
+        assert torch.equal(a.x, b.x)
+    qa.close(); qb.close()

@@ -377,7 +377,9 @@ def main():
                     "scale_pass": {"mode": "filtered" if filtered else "full",
                                    "algorithmic_bytes_per_param": a_scale, "avg_launch_ms": round(scale_avg, 4),
                                    "achieved": gbs(a_scale, scale_avg)},
-                    "whole_step_GBs": gbs(a_main + a_scale, ms_per_step)}
+                    "whole_step_GBs": gbs(a_main + a_scale, ms_per_step),
+                    # the method's own minimum (every buffer once, no read for the scales) over the step time
+                    "a_min_over_step_GBs": gbs(a_main, ms_per_step)}
 
     if args.graph:
         # the passes are not timed one by one inside a graph: report the whole step against the roofline

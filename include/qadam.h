@@ -137,6 +137,26 @@ int qadam_worker_quantize(qadam_handle_t h, int32_t worker, int64_t step,
                           const float* grad_dev, float* err_dev,
                           void* codes_dev, float* scales_dev, void* stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): qadam_worker_quantize for ONE layer segment without a handle and without
+ * any allocation, here or in any routine it calls.  Same results, bit for bit, as qadam_worker_quantize on a
+ * handle with the single segment [0, n), nearest rounding (rounding = 0) and this k_g:
+ *   grad_dev [n] in; err_dev [n] in/out; codes_dev out, ((n+31)/32 * b words rounded up to 4 words) * 4 bytes with
+ *   b = 2, 3, 4 bits for k_g = 0, 1..2, 3..6; scale_dev [1] out (device), ||g+e||_inf.
+ * The per-tile maxima, the reciprocal scale and a status word that the handle keeps in allocated tables live
+ * in a static device array of (QADAM_NOALLOC_MAX_ELEMS / 4096 + 64) * 4 bytes = 256.25 KiB, which each GPU the
+ * library runs on holds until the process ends; n > QADAM_NOALLOC_MAX_ELEMS returns QADAM_ERANGE.  The array's
+ * address on the current device is looked up once per device: by qadam_init, else by the first call of this
+ * function on that device (only that first call should stay outside a graph capture).
+ * ALL calls on one GPU share the array: two calls that may overlap on one GPU (different streams without an
+ * ordering event, or two host threads on different streams) race and give wrong results; calls on one stream
+ * are ordered and need nothing.  Nothing in the array has to be cleared between calls (every word is written
+ * before it is read).  A non-finite ||g+e||_inf is visible in scale_dev (codes are then all zero); there is no
+ * status word to read for this call.  Enqueues three kernels on `stream`; does not synchronise. */
+#define QADAM_NOALLOC_MAX_ELEMS (1 << 28)
+int qadam_quantize_segment_noalloc(int32_t k_g, int64_t n, const float* grad_dev, float* err_dev,
+                                   void* codes_dev, float* scale_dev, void* stream);
+
 /* Server side (mean of the dequantized messages in worker order, moments, parameter step):
  *   codes[i], scales[i]: worker i's outputs of qadam_worker_quantize, i = 0..N-1 (HOST arrays of
  *   device pointers);  x, m, v [P] in/out.  lr = alpha_t, beta2 = theta_t. */

@@ -26,6 +26,7 @@ EXPORTS = [
     "qadam_step_fused", "qadam_worker_step_w", "qadam_server_apply_w", "qadam_step_fused_w", "qadam_weight_dequantize",
     "qadam_weight_dequantize_f16", "qadam_layer_sumsq", "qadam_trust_error_buffers",
     "qadam_get_status", "qadam_last_error", "qadam_profile_enable", "qadam_profile_read",
+    "qadam_quantize_segment_noalloc",
 ]
 
 
@@ -108,6 +109,7 @@ def load_library():
     lib.qadam_last_error.restype = C.c_char_p
     lib.qadam_profile_enable.argtypes = [vp, i32]
     lib.qadam_profile_read.argtypes = [vp, C.POINTER(_Profile)]
+    lib.qadam_quantize_segment_noalloc.argtypes = [i32, i64, vp, vp, vp, vp, vp]
     _lib = lib
     return lib
 
@@ -135,6 +137,18 @@ def _stream(stream) -> Optional[int]:
         import torch
         stream = torch.cuda.current_stream()
     return stream.cuda_stream or None
+
+
+QADAM_NOALLOC_MAX_ELEMS = 1 << 28
+
+
+def quantize_segment_noalloc(k_g, n, grad, err, codes, scale, stream=None):
+    """qadam_quantize_segment_noalloc: one segment, no handle, no allocation (see include/qadam.h)."""
+    lib = load_library()
+    rc = lib.qadam_quantize_segment_noalloc(int(k_g), int(n), _ptr(grad), _ptr(err), _ptr(codes), _ptr(scale),
+                                            _stream(stream))
+    if rc != QADAM_OK:
+        raise QAdamError(rc, (lib.qadam_last_error() or b"").decode())
 
 
 class QAdam:

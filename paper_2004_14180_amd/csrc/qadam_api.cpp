@@ -276,6 +276,9 @@ int qadam_init(qadam_handle_t* out, const qadam_config_t* cfg, const int64_t* se
     h->num_sample_tiles = (int32_t)sample_tiles.size();
 
     hipError_t e = hipGetDevice(&h->device);
+    // set-up of the allocation-free entry point for this device (address of its static array), so that
+    // a caller who created any handle never meets that lookup inside a region that must not allocate
+    if (e == hipSuccess) e = noalloc_prepare();
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&h->d_status), 256);
     if (e == hipSuccess) e = hipMemset(h->d_status, 0, 256);
     if (e == hipSuccess && num_segments > 0)
@@ -368,6 +371,28 @@ int qadam_worker_quantize(qadam_handle_t h, int32_t worker, int64_t step, const 
     QADAM_HIP(launch_reduce_scales(L, S, W, worker, 1));
     QADAM_HIP(launch_worker_quantize(L, S, W, worker));
     record.complete = true;
+    return QADAM_OK;
+}
+
+int qadam_quantize_segment_noalloc(int32_t k_g, int64_t n, const float* grad_dev, float* err_dev,
+                                   void* codes_dev, float* scale_dev, void* stream)
+{
+    if (k_g < 0 || k_g > 6) return fail(QADAM_EINVAL, "k_g outside 0..6");
+    if (n < 0) return fail(QADAM_EINVAL, "n < 0");
+    if (n > kNoallocMaxElems)
+        return fail(QADAM_ERANGE, "segment longer than QADAM_NOALLOC_MAX_ELEMS: use a handle (qadam_worker_quantize)");
+    QADAM_CHECK(check_ptr(grad_dev, "grad_dev", n > 0));
+    QADAM_CHECK(check_ptr(err_dev, "err_dev", n > 0));
+    QADAM_CHECK(check_ptr(codes_dev, "codes_dev", n > 0));
+    QADAM_CHECK(check_ptr(scale_dev, "scale_dev", true));
+    StepScalars S;
+    std::memset(&S, 0, sizeof S);
+    S.num_workers = 1;
+    S.k_g = k_g; S.mu_bits = mu_bits_for(k_g); S.code_bits = 1 + S.mu_bits;
+    S.step = 1;
+    S.n_workers_f = 1.0f; S.inv_n = 1.0f; S.n_is_pow2 = 1;
+    QADAM_HIP(noalloc_quantize_segment(S, n, grad_dev, err_dev, static_cast<uint32_t*>(codes_dev), scale_dev,
+                                       static_cast<hipStream_t>(stream)));
     return QADAM_OK;
 }
 

@@ -28,6 +28,7 @@ constexpr int kTileUnaligned = 1;
 constexpr int kTileSampled = 2;
 constexpr int kSampleStride = 64;   // every 64th tile of a layer (from its first) is a sampled tile
 constexpr int kBlockThreads = 256;
+constexpr int kDefaultTileElems = 4096;   // elements per tile (16 per lane of a 256-thread workgroup)
 
 // Scalars of one launch, identical for every kernel.
 struct StepScalars {
@@ -101,5 +102,14 @@ hipError_t launch_layer_sumsq(const Launch& L, const float* a, const float* b, d
 hipError_t launch_worker_moments_w(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker, int num);
 hipError_t launch_fused_w(const Launch& L, const StepScalars& S, const WorkerPtrs& W, const ServerPtrs& sp);
 hipError_t launch_server_apply_w(const Launch& L, const StepScalars& S, const WorkerPtrs& W, float* x);
+
+
+// Handle-free quantization of one segment (qadam_quantize_segment_noalloc): the per-tile maxima, the
+// reciprocal scale and a status word live in a static device array, so nothing is allocated.
+// noalloc_prepare looks up that array's address on the current device (once per device).
+constexpr int64_t kNoallocMaxElems = QADAM_NOALLOC_MAX_ELEMS;
+hipError_t noalloc_prepare();
+hipError_t noalloc_quantize_segment(const StepScalars& S, int64_t n, const float* grad, float* err, uint32_t* codes,
+                                    float* scale_out, hipStream_t stream);
 
 }  // namespace qadam

@@ -32,6 +32,9 @@
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 
+#include <cstring>
+#include <mutex>
+
 #include "qadam_internal.h"
 
 namespace qadam {
@@ -408,6 +411,7 @@ struct AmaxArgs {
     int num_segments;
     const float* err_bound;     // verification only: [N][L] bounds the error buffers must respect
     uint32_t* status;
+    int64_t seg_len;            // tiles == null only: length of the single segment
 };
 
 struct FusedArgs {
@@ -435,7 +439,29 @@ struct WorkerArgs {        // one worker
     const float* scales;
     const float* inv_scales;   // this worker's row
     int worker;
+    int64_t seg_len;           // tiles == null only: length of the single segment
 };
+
+// Tile record of workgroup `ti`: from the handle's table, or, for the handle-free single-segment
+// call (tiles == null), computed from the segment length: tile ti covers elements
+// [ti * kDefaultTileElems, ...) of a segment that starts 16-byte aligned at element 0.
+__device__ __forceinline__ Tile tile_at(const Tile* __restrict__ tiles, int ti, int64_t seg_len, int code_bits)
+{
+    if (tiles) return tiles[ti];
+    Tile t;
+    t.start = (int64_t)ti * kDefaultTileElems;
+    t.code_word = (int64_t)ti * (kDefaultTileElems / 32) * code_bits;
+    const int64_t left = seg_len - t.start;
+    t.len = (int32_t)(left < kDefaultTileElems ? left : kDefaultTileElems);
+    t.seg = 0;
+    t.flags = 0;
+    if (left <= kDefaultTileElems) {
+        const int64_t used = (seg_len + 31) / 32 * code_bits;
+        t.flags = (int32_t)((used + 3) / 4 * 4 - used) << 8;     // zero words up to a multiple of 16 bytes
+    }
+    t.reserved = 0;
+    return t;
+}
 
 struct ScaleArgs {
     float* scales[QADAM_MAX_WORKERS];
@@ -481,7 +507,9 @@ __device__ __forceinline__ uint32_t block_max(uint32_t local)
 __global__ void __launch_bounds__(kBlockThreads) k_reduce_scales(ScaleArgs A)
 {
     const int l = blockIdx.x, w = A.first_worker + blockIdx.y;
-    const int t0 = A.seg_tile_begin[l], t1 = A.seg_tile_begin[l + 1];
+    // no table: a single segment that owns every tile
+    const int t0 = A.seg_tile_begin ? A.seg_tile_begin[l] : 0;
+    const int t1 = A.seg_tile_begin ? A.seg_tile_begin[l + 1] : A.num_tiles;
     const uint32_t* part = A.tile_max + (size_t)w * A.num_tiles;
     uint32_t local = 0;
     for (int t = t0 + threadIdx.x; t < t1; t += kBlockThreads) {
@@ -569,7 +597,7 @@ __device__ __forceinline__ uint32_t amax_tile(const float* __restrict__ g, const
 __global__ void __launch_bounds__(kBlockThreads) k_amax(AmaxArgs A)
 {
     const int ti = A.tile_list ? A.tile_list[blockIdx.x] : (int)blockIdx.x;
-    const Tile t = A.tiles[ti];
+    const Tile t = tile_at(A.tiles, ti, A.seg_len, 0);
     const int w = A.first_worker + blockIdx.y;
     const float* g = A.grad[w];
     const float* e = A.err[w];
@@ -748,7 +776,7 @@ template <int ROUNDING, bool PARKED>
 __global__ void __launch_bounds__(kBlockThreads) k_worker_quantize(WorkerArgs A)
 {
     const int ti = blockIdx.x;
-    const Tile t = A.tiles[ti];
+    const Tile t = tile_at(A.tiles, ti, A.seg_len, A.S.code_bits);
     if (t.flags & kTileUnaligned) worker_tile<1, ROUNDING, PARKED>(A, t);
     else worker_tile<4, ROUNDING, PARKED>(A, t);
 }
@@ -1229,6 +1257,7 @@ static void fill_amax_args(AmaxArgs& A, const Launch& L, const WorkerPtrs& W, in
     A.first_worker = first_worker;
     A.tile_list = nullptr; A.thr = L.thr; A.num_segments = L.num_segments;
     A.err_bound = L.err_bound; A.status = L.status;
+    A.seg_len = 0;
 }
 
 hipError_t launch_check_error_bounds(const Launch& L, const WorkerPtrs& W, int first_worker, int num)
@@ -1277,6 +1306,7 @@ hipError_t launch_worker_quantize(const Launch& L, const StepScalars& S, const W
     A.grad = W.grad[worker]; A.err = W.err[worker]; A.codes = W.codes[worker]; A.scales = W.scales[worker];
     A.inv_scales = L.inv_scales + (size_t)worker * L.num_segments;
     A.worker = worker;
+    A.seg_len = 0;
     const bool parked = (A.grad == nullptr);
     const dim3 grid(L.num_tiles), block(kBlockThreads);
     if (S.rounding == 0) {
@@ -1442,6 +1472,90 @@ hipError_t launch_worker_moments_w(const Launch& L, const StepScalars& S, const 
     A.tile_max = L.tile_max;
     A.first_worker = first_worker;
     hipLaunchKernelGGL(k_moments_w, dim3(L.num_tiles, num), dim3(kBlockThreads), 0, L.stream, A);
+    return hipGetLastError();
+}
+
+// ================================================================================================
+// Handle-free quantization of one segment without any allocation.
+// The device memory the kernels need beyond the caller's buffers -- one maximum per tile, the
+// reciprocal scale, the residual bound and a status word -- is this file-scope array.  Every GPU
+// holds its own copy at its own address; host code must never pass the array's name to a kernel
+// or a HIP call (on the host it is only a stand-in for the symbol): it uses the address that
+// hipGetSymbolAddress returned for the current device.
+// ================================================================================================
+constexpr int kNoallocMaxTiles = (int)(kNoallocMaxElems / kDefaultTileElems);
+constexpr int kNoallocExtraWords = 64;      // [0] reciprocal scale, [1] residual bound, [2] status, rest unused
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) uint32_t scratch[kNoallocMaxTiles + kNoallocExtraWords];
+
+static uint32_t* g_scratch_ptr[kMaxDevices];          // per device, null until looked up
+static std::mutex g_scratch_mutex;
+
+static hipError_t scratch_for_current_device(uint32_t** out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = static_cast<uint32_t*>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+
+hipError_t noalloc_prepare()
+{
+    uint32_t* p = nullptr;
+    return scratch_for_current_device(&p);
+}
+
+// The three launches of qadam_worker_quantize for worker 0 of a one-segment vector of n elements,
+// with tile records computed in the kernels and the scratch rows taken from the static array.
+// Nothing of the array has to start at zero: every tile maximum, the reciprocal and the bound are
+// written before they are read, and the status word is only ever OR-ed into and never read here.
+hipError_t noalloc_quantize_segment(const StepScalars& S, int64_t n, const float* grad, float* err, uint32_t* codes,
+                                    float* scale_out, hipStream_t stream)
+{
+    uint32_t* sc = nullptr;
+    hipError_t e = scratch_for_current_device(&sc);
+    if (e != hipSuccess) return e;
+    const int num_tiles = (int)((n + kDefaultTileElems - 1) / kDefaultTileElems);
+    uint32_t* tile_max = sc;
+    float* inv_scale = reinterpret_cast<float*>(sc + kNoallocMaxTiles);
+    float* err_bound = reinterpret_cast<float*>(sc + kNoallocMaxTiles + 1);
+    uint32_t* status = sc + kNoallocMaxTiles + 2;
+
+    if (num_tiles > 0) {
+        AmaxArgs A;
+        std::memset(&A, 0, sizeof A);
+        A.tiles = nullptr; A.num_tiles = num_tiles; A.seg_len = n;
+        A.grad[0] = grad; A.err[0] = err;
+        A.tile_max = tile_max; A.first_worker = 0; A.num_segments = 1; A.status = status;
+        hipLaunchKernelGGL(k_amax, dim3(num_tiles, 1), dim3(kBlockThreads), 0, stream, A);
+    }
+    ScaleArgs R;
+    std::memset(&R, 0, sizeof R);
+    R.scales[0] = scale_out; R.inv_scales = inv_scale; R.tile_max = tile_max; R.seg_tile_begin = nullptr;
+    R.first_worker = 0; R.num_segments = 1; R.num_tiles = num_tiles;
+    R.err_bound = err_bound; R.thr = nullptr;
+    R.bound_factor = residual_bound_factor(S);
+    R.sample_stride = kSampleStride;
+    hipLaunchKernelGGL(k_reduce_scales, dim3(1, 1), dim3(kBlockThreads), 0, stream, R);
+    if (num_tiles > 0) {
+        WorkerArgs W;
+        std::memset(&W, 0, sizeof W);
+        W.tiles = nullptr; W.num_tiles = num_tiles; W.seg_len = n;
+        W.status = status; W.S = S;
+        W.grad = grad; W.err = err; W.codes = codes; W.scales = scale_out; W.inv_scales = inv_scale;
+        W.worker = 0;
+        hipLaunchKernelGGL((k_worker_quantize<0, false>), dim3(num_tiles), dim3(kBlockThreads), 0, stream, W);
+    }
     return hipGetLastError();
 }
 

@@ -26,7 +26,7 @@ EXPORTS = [
     "qadam_step_fused", "qadam_worker_step_w", "qadam_server_apply_w", "qadam_step_fused_w", "qadam_weight_dequantize",
     "qadam_weight_dequantize_f16", "qadam_layer_sumsq", "qadam_trust_error_buffers",
     "qadam_get_status", "qadam_last_error", "qadam_profile_enable", "qadam_profile_read",
-    "qadam_quantize_segment_noalloc",
+    "qadam_quantize_segment_noalloc", "qadam_arena_layout",
 ]
 
 
@@ -44,6 +44,12 @@ class _Config(C.Structure):
 
 class _Profile(C.Structure):
     _fields_ = [("scale_pass_ms", C.c_float), ("main_pass_ms", C.c_float)]
+
+
+class _Arena(C.Structure):
+    _fields_ = [(n, C.c_size_t) for n in ("x", "m", "v", "werr", "wcodes")] + \
+               [(n, C.c_size_t * QADAM_MAX_WORKERS) for n in ("grads", "errs", "codes", "scales", "mw", "vw")] + \
+               [("bytes_needed", C.c_size_t)]
 
 
 class _Status(C.Structure):
@@ -110,6 +116,7 @@ def load_library():
     lib.qadam_profile_enable.argtypes = [vp, i32]
     lib.qadam_profile_read.argtypes = [vp, C.POINTER(_Profile)]
     lib.qadam_quantize_segment_noalloc.argtypes = [i32, i64, vp, vp, vp, vp, vp]
+    lib.qadam_arena_layout.argtypes = [vp, C.c_size_t, i32, C.POINTER(_Arena)]
     _lib = lib
     return lib
 
@@ -198,50 +205,149 @@ class QAdam:
     def weight_code_bytes(self) -> int:
         return int(self._lib.qadam_weight_code_bytes(self._h))
 
+    # argument checks ---------------------------------------------------------------------------
+    # The kernels write P-sized streams through the raw addresses they are given, so a buffer of the
+    # wrong type, size or device would be an out-of-bounds device access: refuse it here.
+    def _buf(self, t, name, numel, kind="f32", optional=False):
+        """Device address of tensor `t` after checking device, layout, element type and size."""
+        import torch
+        if t is None:
+            if optional:
+                return None
+            raise ValueError("%s is required" % name)
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError("%s: expected a contiguous device tensor" % name)
+        if t.device.index != torch.cuda.current_device():
+            raise ValueError("%s lives on %s, the current device is %d" % (name, t.device, torch.cuda.current_device()))
+        if kind == "f32":
+            if t.dtype != torch.float32:
+                raise ValueError("%s: expected float32, got %s" % (name, t.dtype))
+            have = t.numel()
+        elif kind == "f16":
+            if t.dtype != torch.float16:
+                raise ValueError("%s: expected float16, got %s" % (name, t.dtype))
+            have = t.numel()
+        elif kind == "f64":
+            if t.dtype != torch.float64:
+                raise ValueError("%s: expected float64, got %s" % (name, t.dtype))
+            have = t.numel()
+        else:                                   # "bytes": any integer type, size counted in bytes
+            if t.dtype.is_floating_point or t.dtype.is_complex:
+                raise ValueError("%s: expected an integer tensor, got %s" % (name, t.dtype))
+            have = t.numel() * t.element_size()
+        if have < numel:
+            raise ValueError("%s holds %d %s, the call needs %d" % (name, have, "bytes" if kind == "bytes" else "elements", numel))
+        return t.data_ptr()
+
+    def _bufs(self, ts, name, numel, kind="f32", optional=False):
+        if ts is None:
+            if optional:
+                return None
+            raise ValueError("%s is required" % name)
+        if len(ts) != self.num_workers:
+            raise ValueError("%s: expected %d tensors (one per worker), got %d" % (name, self.num_workers, len(ts)))
+        arr = (C.c_void_p * len(ts))()
+        for i, t in enumerate(ts):
+            arr[i] = self._buf(t, "%s[%d]" % (name, i), numel, kind)
+        return arr
+
     # the calls ---------------------------------------------------------------------------------
     def worker_quantize(self, worker, step, grad, err, codes, scales, stream=None):
-        self._check(self._lib.qadam_worker_quantize(self._h, worker, step, _ptr(grad), _ptr(err),
-                                                    _ptr(codes), _ptr(scales), _stream(stream)))
+        P, L = self.num_params, self.num_segments
+        self._check(self._lib.qadam_worker_quantize(
+            self._h, worker, step, self._buf(grad, "grad", P), self._buf(err, "err", P),
+            self._buf(codes, "codes", self.grad_code_bytes(), "bytes"), self._buf(scales, "scales", L),
+            _stream(stream)))
 
     def server_step(self, step, lr, beta2, codes, scales, x, m, v, stream=None):
-        self._check(self._lib.qadam_server_step(self._h, step, lr, beta2, _ptr_array(codes),
-                                                _ptr_array(scales), _ptr(x), _ptr(m), _ptr(v),
-                                                _stream(stream)))
+        P, L = self.num_params, self.num_segments
+        self._check(self._lib.qadam_server_step(
+            self._h, step, lr, beta2, self._bufs(codes, "codes", self.grad_code_bytes(), "bytes"),
+            self._bufs(scales, "scales", L), self._buf(x, "x", P), self._buf(m, "m", P), self._buf(v, "v", P),
+            _stream(stream)))
 
     def weight_quantize(self, step, x, werr, wcodes, stream=None):
-        self._check(self._lib.qadam_weight_quantize(self._h, step, _ptr(x), _ptr(werr), _ptr(wcodes),
-                                                    _stream(stream)))
+        P = self.num_params
+        self._check(self._lib.qadam_weight_quantize(
+            self._h, step, self._buf(x, "x", P), self._buf(werr, "werr", P, optional=self.cfg.weight_ef == 0),
+            self._buf(wcodes, "wcodes", self.weight_code_bytes(), "bytes"), _stream(stream)))
+
+    def _server_side(self, werr, wcodes):
+        idx = self.cfg.k_x == QADAM_IDENTITY
+        P = self.num_params
+        if idx:                                     # Q_x = id: no weight codes, no residual
+            return None, None
+        return (self._buf(werr, "werr", P, optional=self.cfg.weight_ef == 0),
+                self._buf(wcodes, "wcodes", self.weight_code_bytes(), "bytes"))
 
     def step_fused(self, step, lr, beta2, grads, errs, codes, scales, x, m, v, werr, wcodes, stream=None):
-        self._check(self._lib.qadam_step_fused(self._h, step, lr, beta2, _ptr_array(grads),
-                                               _ptr_array(errs), _ptr_array(codes), _ptr_array(scales),
-                                               _ptr(x), _ptr(m), _ptr(v), _ptr(werr), _ptr(wcodes),
-                                               _stream(stream)))
+        P, L = self.num_params, self.num_segments
+        idg = self.cfg.k_g == QADAM_IDENTITY
+        pw, pc = self._server_side(werr, wcodes)
+        self._check(self._lib.qadam_step_fused(
+            self._h, step, lr, beta2, self._bufs(grads, "grads", P),
+            None if idg else self._bufs(errs, "errs", P),          # Q_g = id: errs, codes, scales are not used
+            None if idg else self._bufs(codes, "codes", self.grad_code_bytes(), "bytes"),
+            None if idg else self._bufs(scales, "scales", L), self._buf(x, "x", P), self._buf(m, "m", P),
+            self._buf(v, "v", P), pw, pc, _stream(stream)))
 
     def worker_step_w(self, worker, step, lr, beta2, grad, mw, vw, err, codes, scales, stream=None):
-        self._check(self._lib.qadam_worker_step_w(self._h, worker, step, lr, beta2, _ptr(grad), _ptr(mw),
-                                                  _ptr(vw), _ptr(err), _ptr(codes), _ptr(scales),
-                                                  _stream(stream)))
+        P, L = self.num_params, self.num_segments
+        self._check(self._lib.qadam_worker_step_w(
+            self._h, worker, step, lr, beta2, self._buf(grad, "grad", P), self._buf(mw, "mw", P),
+            self._buf(vw, "vw", P), self._buf(err, "err", P),
+            self._buf(codes, "codes", self.grad_code_bytes(), "bytes"), self._buf(scales, "scales", L),
+            _stream(stream)))
 
     def step_fused_w(self, step, lr, beta2, grads, mw, vw, errs, codes, scales, x, werr, wcodes, stream=None):
-        self._check(self._lib.qadam_step_fused_w(self._h, step, lr, beta2, _ptr_array(grads), _ptr_array(mw),
-                                                 _ptr_array(vw), _ptr_array(errs), _ptr_array(codes),
-                                                 _ptr_array(scales), _ptr(x), _ptr(werr), _ptr(wcodes),
-                                                 _stream(stream)))
+        P, L = self.num_params, self.num_segments
+        idg = self.cfg.k_g == QADAM_IDENTITY
+        pw, pc = self._server_side(werr, wcodes)
+        self._check(self._lib.qadam_step_fused_w(
+            self._h, step, lr, beta2, self._bufs(grads, "grads", P), self._bufs(mw, "mw", P),
+            self._bufs(vw, "vw", P), self._bufs(errs, "errs", P),
+            None if idg else self._bufs(codes, "codes", self.grad_code_bytes(), "bytes"),
+            None if idg else self._bufs(scales, "scales", L), self._buf(x, "x", P), pw, pc, _stream(stream)))
 
     def server_apply_w(self, step, codes, scales, x, stream=None):
-        self._check(self._lib.qadam_server_apply_w(self._h, step, _ptr_array(codes), _ptr_array(scales),
-                                                   _ptr(x), _stream(stream)))
+        P, L = self.num_params, self.num_segments
+        self._check(self._lib.qadam_server_apply_w(
+            self._h, step, self._bufs(codes, "codes", self.grad_code_bytes(), "bytes"),
+            self._bufs(scales, "scales", L), self._buf(x, "x", P), _stream(stream)))
 
     def weight_dequantize(self, wcodes, xhat, stream=None):
-        self._check(self._lib.qadam_weight_dequantize(self._h, _ptr(wcodes), _ptr(xhat), _stream(stream)))
+        self._check(self._lib.qadam_weight_dequantize(
+            self._h, self._buf(wcodes, "wcodes", self.weight_code_bytes(), "bytes"),
+            self._buf(xhat, "xhat", self.num_params), _stream(stream)))
 
     def weight_dequantize_f16(self, wcodes, xhat_half, stream=None):
-        self._check(self._lib.qadam_weight_dequantize_f16(self._h, _ptr(wcodes), _ptr(xhat_half), _stream(stream)))
+        self._check(self._lib.qadam_weight_dequantize_f16(
+            self._h, self._buf(wcodes, "wcodes", self.weight_code_bytes(), "bytes"),
+            self._buf(xhat_half, "xhat_half", self.num_params, "f16"), _stream(stream)))
 
     def layer_sumsq(self, a, b, out, stream=None):
         """out[l] = sum over layer l of (a + b)^2 in fp64 (b may be None)."""
-        self._check(self._lib.qadam_layer_sumsq(self._h, _ptr(a), _ptr(b), _ptr(out), _stream(stream)))
+        P = self.num_params
+        self._check(self._lib.qadam_layer_sumsq(self._h, self._buf(a, "a", P), self._buf(b, "b", P, optional=True),
+                                                self._buf(out, "out", self.num_segments, "f64"), _stream(stream)))
+
+    def arena_layout(self, arena_bytes, with_worker_moments=False):
+        """qadam_arena_layout: dict of byte offsets (lists per worker) inside one caller-allocated block;
+        `bytes_needed` is the smallest block that fits.  Host arithmetic only."""
+        a = _Arena()
+        rc = self._lib.qadam_arena_layout(self._h, int(arena_bytes), int(bool(with_worker_moments)), C.byref(a))
+        if rc == QADAM_ERANGE:
+            raise QAdamError(rc, "the block of %d bytes is smaller than the %d bytes the buffers need"
+                             % (arena_bytes, a.bytes_needed))
+        self._check(rc)
+        N = self.num_workers
+        out = {n: int(getattr(a, n)) for n in ("x", "m", "v", "werr", "wcodes", "bytes_needed")}
+        for n in ("grads", "errs", "codes", "scales"):
+            out[n] = [int(getattr(a, n)[i]) for i in range(N)]
+        if with_worker_moments:
+            for n in ("mw", "vw"):
+                out[n] = [int(getattr(a, n)[i]) for i in range(N)]
+        return out
 
     def trust_error_buffers(self, on=1):
         """Opt in to the filtered scale pass (see include/qadam.h for the contract):

@@ -11,7 +11,12 @@ LIB = os.path.join(HERE, "libqadam_hip.so")
 SOURCES = ["qadam_kernels.hip", "qadam_api.cpp"]
 
 # -ffp-contract=off: one rounding per operation, so integer codes are reproducible bit for bit.
-# The target-feature switch keeps the compiler from forming packed-fp32 instructions.
+# The target-feature switch keeps the gfx950 pass from forming packed-fp32 instructions (v_pk_add_f32,
+# v_pk_mul_f32, v_pk_fma_f32): with it the device assembly of qadam_kernels.hip holds none of them, without
+# it several hundred (tests/test_library_boundary.py checks this).  -Xclang options reach both passes of
+# hipcc, and the HOST (x86-64) pass does not know the feature: it prints "'-packed-fp32-ops' is not a
+# recognized feature for this target (ignoring feature)" once per function it compiles.  That warning is
+# the host pass's and is harmless; the device pass honours the switch silently.
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-ffp-contract=off", "-fno-fast-math",
@@ -25,6 +30,32 @@ def hipcc() -> str:
         if cand and (os.path.sep not in cand or os.path.exists(cand)):
             return cand
     raise RuntimeError("hipcc not found")
+
+
+PROBE_SRC = os.path.join(CSRC, "qadam_probe.hip")
+PROBE = os.path.join(HERE, "qadam_probe.bin")
+
+
+def build_probe(verbose: bool = True) -> str:
+    """The stand-alone memory-system probes (measurement aid, not part of the library)."""
+    tmp = PROBE + ".tmp%d" % os.getpid()
+    cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", "-o", tmp, PROBE_SRC]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    os.replace(tmp, PROBE)
+    return PROBE
+
+
+def device_assembly(source: str = "qadam_kernels.hip", packed_fp32_off: bool = True) -> str:
+    """gfx950 assembly text of one of this package's own sources (for checks of what the compiler emitted)."""
+    flags = [f for f in HIPCC_FLAGS if f not in ("-fPIC", "-shared")]
+    if not packed_fp32_off:
+        flags = [f for f in flags if f not in ("-Xclang", "-target-feature", "-packed-fp32-ops")]
+    cmd = [hipcc(), *flags, "--cuda-device-only", "-S", "-I", os.path.join(HERE, "..", "include"), "-o", "-",
+           os.path.join(CSRC, source)]
+    return subprocess.run(cmd, check=True, capture_output=True, text=True).stdout
 
 
 def build_library(verbose: bool = True) -> str:
@@ -43,4 +74,5 @@ def build_library(verbose: bool = True) -> str:
 
 if __name__ == "__main__":
     build_library()
+    build_probe()
     sys.exit(0)

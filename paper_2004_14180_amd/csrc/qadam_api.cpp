@@ -31,8 +31,10 @@ struct qadam_ctx {
     uint32_t* d_thr;            // [num_workers][num_segments]
     int32_t*  d_sample_tiles;   // indices of the sampled tiles
     int32_t   num_sample_tiles;
+    bool      all_small;        // every layer is a small layer (handled by one workgroup, no scale pass)
     int       trust_errs;                       // qadam_trust_error_buffers: 0 off, 1 when it pays, 2 always, 3 verify
-    bool      bound_valid[QADAM_MAX_WORKERS];   // d_err_bound row i describes what errs[i] now holds
+    bool      bound_valid[QADAM_MAX_WORKERS];   // d_err_bound row i describes what bound_err[i] now holds
+    const float* bound_err[QADAM_MAX_WORKERS];  // the error buffer that row was recorded for
     bool       profile;
     bool       profile_valid;
     hipEvent_t ev[3];
@@ -60,6 +62,11 @@ int fail(int code, const char* msg)
     return code;
 }
 
+// qadam_trust_error_buffers(h, 1): smallest number of (tile, worker) pairs of a call for which the filtered
+// scale pass, with its two extra launches, is faster than the full one (measured: slower on a 4-worker,
+// 11.7 M-parameter vector, 6 % faster on an 8-worker, 124 M-parameter one)
+constexpr int64_t kFilterMinTiles = 32768;
+
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 int mu_bits_for(int k_g)
@@ -73,17 +80,6 @@ int64_t segment_code_words(int code_bits, int64_t n)
 {
     const int64_t words = (n + 31) / 32 * code_bits;
     return (words + 3) / 4 * 4;
-}
-
-int tile_elems_from_env()
-{
-    // tuning knob for experiments; the default is what the library is measured with
-    const char* s = std::getenv("QADAM_TILE_ELEMS");
-    if (s) {
-        const long v = std::strtol(s, nullptr, 10);
-        if (v >= 256 && v <= (1 << 20) && v % 256 == 0) return (int)v;
-    }
-    return 4096;
 }
 
 StepScalars make_scalars(const qadam_ctx* h, int64_t step, float lr, float beta2)
@@ -120,6 +116,7 @@ Launch make_launch(const qadam_ctx* h, void* stream)
     L.sample_tiles = h->d_sample_tiles; L.num_sample_tiles = h->num_sample_tiles;
     L.num_tiles = h->num_tiles; L.num_segments = h->num_segments;
     L.num_params = h->num_params; L.status = h->d_status; L.stream = static_cast<hipStream_t>(stream);
+    L.all_small = h->all_small;
     return L;
 }
 
@@ -152,15 +149,43 @@ struct BoundRecord {
     qadam_ctx* h;
     int first, num;
     bool complete;
-    BoundRecord(qadam_ctx* h_, int first_, int num_) : h(h_), first(first_), num(num_), complete(false)
+    BoundRecord(qadam_ctx* h_, int first_, int num_, const WorkerPtrs& W) : h(h_), first(first_), num(num_), complete(false)
     {
-        for (int i = first; i < first + num; ++i) h->bound_valid[i] = false;
+        for (int i = first; i < first + num; ++i) {
+            h->bound_valid[i] = false;
+            h->bound_err[i] = W.err[i];
+        }
     }
     ~BoundRecord()
     {
         for (int i = first; i < first + num; ++i) h->bound_valid[i] = complete;
     }
 };
+
+// The recorded bound of worker i can be used for this call: it is valid and was recorded for the very
+// buffer the caller passes now (another buffer, e.g. a restored checkpoint, gets the full scale pass).
+bool bound_usable(const qadam_ctx* h, int i, const float* err) { return h->bound_valid[i] && h->bound_err[i] == err; }
+
+// Is the stream recording a HIP graph?  A captured call is replayed later with the kernel arguments
+// it was recorded with, so what depends on the step number must not be captured.
+int stream_capturing(void* stream, bool* capturing)
+{
+    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+    QADAM_HIP(hipStreamIsCapturing(static_cast<hipStream_t>(stream), &st));
+    *capturing = st != hipStreamCaptureStatusNone;
+    return QADAM_OK;
+}
+
+// Refuses to record a call whose kernel arguments change from step to step in a way a replay cannot
+// follow: the Philox counter (rounding = 1) and the bias corrections (adam_flavor = 1).
+int check_capture(const qadam_ctx* h, void* stream, bool* capturing)
+{
+    QADAM_CHECK(stream_capturing(stream, capturing));
+    if (*capturing && (h->cfg.rounding == 1 || h->cfg.adam_flavor == 1))
+        return fail(QADAM_EINVAL, "stream is capturing a graph: a replay would reuse this step's random stream "
+                                  "(rounding = 1) or bias correction (adam_flavor = 1)");
+    return QADAM_OK;
+}
 
 bool identity_g(const qadam_ctx* h) { return h->cfg.k_g == QADAM_IDENTITY; }
 bool identity_x(const qadam_ctx* h) { return h->cfg.k_x == QADAM_IDENTITY; }
@@ -230,7 +255,7 @@ int qadam_init(qadam_handle_t* out, const qadam_config_t* cfg, const int64_t* se
     h->mu_bits = cfg->k_g == QADAM_IDENTITY ? 0 : mu_bits_for(cfg->k_g);
     h->code_bits = cfg->k_g == QADAM_IDENTITY ? 0 : 1 + h->mu_bits;       /* 0: no codes are stored */
     h->wcode_bytes = cfg->k_x == QADAM_IDENTITY ? 0 : (cfg->k_x <= 6 ? 1 : 2);
-    h->tile_elems = tile_elems_from_env();
+    h->tile_elems = kDefaultTileElems;
 
     // one workgroup per tile: a launch needs tiles * threads per workgroup below 2^32
     int64_t tile_count = 0;
@@ -247,11 +272,13 @@ int qadam_init(qadam_handle_t* out, const qadam_config_t* cfg, const int64_t* se
     std::vector<int32_t> sample_tiles;
     std::vector<int32_t> seg_tile_begin(num_segments + 1, 0);
     int64_t word_off = 0;
+    bool all_small = true;
     for (int l = 0; l < num_segments; ++l) {
         seg_tile_begin[l] = (int32_t)tiles.size();
         const int64_t a = seg_offsets[l], n = seg_offsets[l + 1] - a;
         const int64_t seg_words = segment_code_words(h->code_bits, n);
         const int64_t used_words = (n + 31) / 32 * h->code_bits;
+        if (n == 0) all_small = false;          // an empty layer's scale (0) is written by the scale kernel
         for (int64_t o = 0; o < n; o += h->tile_elems) {
             Tile t;
             t.start = a + o;
@@ -260,11 +287,18 @@ int qadam_init(qadam_handle_t* out, const qadam_config_t* cfg, const int64_t* se
             t.seg = l;
             t.flags = (a % 4 != 0) ? kTileUnaligned : 0;
             if (o + h->tile_elems >= n) t.flags |= (int32_t)(seg_words - used_words) << 8;
-            if ((o / h->tile_elems) % kSampleStride == 0) {
-                t.flags |= kTileSampled;
-                sample_tiles.push_back((int32_t)tiles.size());
+            t.layer_len = 0;
+            if (n <= kSmallLayerElems) {
+                // one workgroup (that of the first tile) handles the whole layer; never a sampled tile
+                t.flags |= o == 0 ? kTileSmallHead : kTileSmallBody;
+                if (o == 0) t.layer_len = (int32_t)n;
+            } else {
+                all_small = false;
+                if ((o / h->tile_elems) % kSampleStride == 0) {
+                    t.flags |= kTileSampled;
+                    sample_tiles.push_back((int32_t)tiles.size());
+                }
             }
-            t.reserved = 0;
             tiles.push_back(t);
         }
         word_off += seg_words;
@@ -274,6 +308,7 @@ int qadam_init(qadam_handle_t* out, const qadam_config_t* cfg, const int64_t* se
     seg_tile_begin[num_segments] = (int32_t)tiles.size();
     h->num_tiles = (int32_t)tiles.size();
     h->num_sample_tiles = (int32_t)sample_tiles.size();
+    h->all_small = all_small;
 
     hipError_t e = hipGetDevice(&h->device);
     // set-up of the allocation-free entry point for this device (address of its static array), so that
@@ -362,15 +397,18 @@ int qadam_worker_quantize(qadam_handle_t h, int32_t worker, int64_t step, const 
     W.codes[worker] = static_cast<uint32_t*>(codes_dev); W.scales[worker] = scales_dev;
     const StepScalars S = make_scalars(h, step, 0.0f, 0.0f);
     const Launch L = make_launch(h, stream);
-    const bool filtered = h->bound_valid[worker] &&
-                          (h->trust_errs == 2 || (h->trust_errs == 1 && h->num_tiles >= 4096));
-    if (h->trust_errs == 3 && h->bound_valid[worker]) QADAM_HIP(launch_check_error_bounds(L, W, worker, 1));
-    BoundRecord record(h, worker, 1);
+    bool capturing = false;
+    QADAM_CHECK(check_capture(h, stream, &capturing));
+    // a recorded call always takes the full scale pass: a replay must not depend on what ran before it
+    const bool recorded = !capturing && bound_usable(h, worker, err_dev);
+    const bool filtered = recorded && (h->trust_errs == 2 || (h->trust_errs == 1 && h->num_tiles >= kFilterMinTiles));
+    if (h->trust_errs == 3 && recorded) QADAM_HIP(launch_check_error_bounds(L, W, worker, 1));
+    BoundRecord record(h, worker, 1, W);
     if (filtered) QADAM_HIP(launch_amax_filtered(L, S, W, worker, 1));
     else QADAM_HIP(launch_amax(L, S, W, worker, 1));
-    QADAM_HIP(launch_reduce_scales(L, S, W, worker, 1));
+    QADAM_HIP(launch_reduce_scales(L, S, W, worker, 1, true));
     QADAM_HIP(launch_worker_quantize(L, S, W, worker));
-    record.complete = true;
+    record.complete = !capturing;       // nothing has run yet when the call was only recorded
     return QADAM_OK;
 }
 
@@ -412,6 +450,8 @@ int qadam_server_step(qadam_handle_t h, int64_t step, float lr, float beta2, con
     ServerPtrs sp;
     sp.x = x_dev; sp.m = m_dev; sp.v = v_dev; sp.werr = nullptr; sp.wcodes = nullptr;
     const StepScalars S = make_scalars(h, step, lr, beta2);
+    bool capturing = false;
+    QADAM_CHECK(check_capture(h, stream, &capturing));
     QADAM_HIP(launch_server_step(make_launch(h, stream), S, W, sp));
     return QADAM_OK;
 }
@@ -427,6 +467,8 @@ int qadam_weight_quantize(qadam_handle_t h, int64_t step, const float* x_dev, fl
     QADAM_CHECK(check_ptr(werr_dev, "werr_dev", !empty && h->cfg.weight_ef == 1));
     QADAM_CHECK(check_ptr(wcodes_dev, "wcodes_dev", !empty));
     const StepScalars S = make_scalars(h, step, 0.0f, 0.0f);
+    bool capturing = false;
+    QADAM_CHECK(check_capture(h, stream, &capturing));
     QADAM_HIP(launch_weight_quantize(make_launch(h, stream), S, x_dev, werr_dev, wcodes_dev));
     return QADAM_OK;
 }
@@ -475,28 +517,31 @@ int qadam_step_fused(qadam_handle_t h, int64_t step, float lr, float beta2, cons
     sp.werr = idx ? nullptr : werr_dev; sp.wcodes = idx ? nullptr : wcodes_dev;
     const StepScalars S = make_scalars(h, step, lr, beta2);
     const Launch L = make_launch(h, stream);
-    if (h->profile) QADAM_HIP(hipEventRecord(h->ev[0], L.stream));
+    bool capturing = false;
+    QADAM_CHECK(check_capture(h, stream, &capturing));
+    if (h->profile && !capturing) QADAM_HIP(hipEventRecord(h->ev[0], L.stream));
     if (idg) {
         // the error buffers are not touched: whatever is recorded about them stays true
-        if (h->profile) QADAM_HIP(hipEventRecord(h->ev[1], L.stream));
+        if (h->profile && !capturing) QADAM_HIP(hipEventRecord(h->ev[1], L.stream));
         QADAM_HIP(launch_plain_messages(L, S, W, sp, false));
     } else {
-        // the filtered pass costs two more (small) launches: only worth it beyond a few million worker-elements
+        // the filtered pass costs two more (small) launches: only worth it from about 10^8 worker-elements on
         bool filtered = h->trust_errs == 2 ||
-                        (h->trust_errs == 1 && (int64_t)h->num_tiles * h->num_workers >= 4096);
+                        (h->trust_errs == 1 && (int64_t)h->num_tiles * h->num_workers >= kFilterMinTiles);
         bool all_recorded = true;
-        for (int i = 0; i < h->num_workers; ++i) all_recorded = all_recorded && h->bound_valid[i];
+        for (int i = 0; i < h->num_workers; ++i) all_recorded = all_recorded && bound_usable(h, i, W.err[i]);
+        all_recorded = all_recorded && !capturing;     // a recorded call always takes the full scale pass
         filtered = filtered && all_recorded;
         if (h->trust_errs == 3 && all_recorded) QADAM_HIP(launch_check_error_bounds(L, W, 0, h->num_workers));
-        BoundRecord record(h, 0, h->num_workers);
+        BoundRecord record(h, 0, h->num_workers, W);
         if (filtered) QADAM_HIP(launch_amax_filtered(L, S, W, 0, h->num_workers));
         else QADAM_HIP(launch_amax(L, S, W, 0, h->num_workers));
-        QADAM_HIP(launch_reduce_scales(L, S, W, 0, h->num_workers));
-        if (h->profile) QADAM_HIP(hipEventRecord(h->ev[1], L.stream));
+        QADAM_HIP(launch_reduce_scales(L, S, W, 0, h->num_workers, true));
+        if (h->profile && !capturing) QADAM_HIP(hipEventRecord(h->ev[1], L.stream));
         QADAM_HIP(launch_fused(L, S, W, sp));
-        record.complete = true;
+        record.complete = !capturing;
     }
-    if (h->profile) {
+    if (h->profile && !capturing) {
         QADAM_HIP(hipEventRecord(h->ev[2], L.stream));
         h->profile_valid = true;
     }
@@ -524,14 +569,16 @@ int qadam_worker_step_w(qadam_handle_t h, int32_t worker, int64_t step, float lr
     W.codes[worker] = static_cast<uint32_t*>(codes_dev); W.scales[worker] = scales_dev;
     const StepScalars S = make_scalars(h, step, lr, beta2);
     const Launch L = make_launch(h, stream);
+    bool capturing = false;
+    QADAM_CHECK(check_capture(h, stream, &capturing));
     // pass 1: local moments, p = alpha m / sqrt(v + eps) + e parked in the error buffer, tile maxima
-    BoundRecord record(h, worker, 1);
+    BoundRecord record(h, worker, 1, W);
     QADAM_HIP(launch_worker_moments_w(L, S, W, worker, 1));
-    QADAM_HIP(launch_reduce_scales(L, S, W, worker, 1));
+    QADAM_HIP(launch_reduce_scales(L, S, W, worker, 1, false));
     // pass 2: quantize the parked p
     W.grad[worker] = nullptr;
     QADAM_HIP(launch_worker_quantize(L, S, W, worker));
-    record.complete = true;
+    record.complete = !capturing;
     return QADAM_OK;
 }
 
@@ -559,17 +606,19 @@ int qadam_step_fused_w(qadam_handle_t h, int64_t step, float lr, float beta2, co
     sp.werr = idx ? nullptr : werr_dev; sp.wcodes = idx ? nullptr : wcodes_dev;
     const StepScalars S = make_scalars(h, step, lr, beta2);
     const Launch L = make_launch(h, stream);
-    if (h->profile) QADAM_HIP(hipEventRecord(h->ev[0], L.stream));
+    bool capturing = false;
+    QADAM_CHECK(check_capture(h, stream, &capturing));
+    if (h->profile && !capturing) QADAM_HIP(hipEventRecord(h->ev[0], L.stream));
     // pass 1 (all workers): local moments, p parked in the error buffers, tile maxima; then scales
-    BoundRecord record(h, 0, h->num_workers);
+    BoundRecord record(h, 0, h->num_workers, W);
     QADAM_HIP(launch_worker_moments_w(L, S, W, 0, h->num_workers));
-    if (!idg) QADAM_HIP(launch_reduce_scales(L, S, W, 0, h->num_workers));
-    if (h->profile) QADAM_HIP(hipEventRecord(h->ev[1], L.stream));
+    if (!idg) QADAM_HIP(launch_reduce_scales(L, S, W, 0, h->num_workers, false));
+    if (h->profile && !capturing) QADAM_HIP(hipEventRecord(h->ev[1], L.stream));
     // pass 2: quantize every worker's parked p, subtract the mean message, Q_x
     if (idg) QADAM_HIP(launch_plain_messages(L, S, W, sp, true));
     else QADAM_HIP(launch_fused_w(L, S, W, sp));
-    record.complete = !idg;     // with the identity quantizer no scale, hence no bound, was produced
-    if (h->profile) {
+    record.complete = !idg && !capturing;   // with the identity quantizer no scale, hence no bound, was produced
+    if (h->profile && !capturing) {
         QADAM_HIP(hipEventRecord(h->ev[2], L.stream));
         h->profile_valid = true;
     }
@@ -598,6 +647,47 @@ int qadam_layer_sumsq(qadam_handle_t h, const float* a_dev, const float* b_dev, 
     QADAM_CHECK(check_ptr(b_dev, "b_dev", false));
     QADAM_CHECK(check_ptr(out_dev, "out_dev", h->num_segments > 0));
     QADAM_HIP(launch_layer_sumsq(make_launch(h, stream), a_dev, b_dev, out_dev));
+    return QADAM_OK;
+}
+
+int qadam_arena_layout(qadam_handle_t h, size_t arena_bytes, int32_t with_worker_moments, qadam_arena_t* out)
+{
+    if (!h) return fail(QADAM_EINVAL, "null handle");
+    if (!out) return fail(QADAM_EINVAL, "null layout");
+    std::memset(out, 0xff, sizeof *out);            // every entry SIZE_MAX until placed
+    const int N = h->num_workers;
+    constexpr size_t align = 2u << 20;              // buffers start on 2 MiB boundaries (the driver's large pages)
+    auto rup = [](size_t n) { return (n + align - 1) / align * align; };
+    const size_t big = rup((size_t)h->num_params * 4u);
+    const size_t code = rup(qadam_grad_code_bytes(h));
+    const size_t wcode = rup(qadam_weight_code_bytes(h));
+    const size_t scale = rup((size_t)h->num_segments * 4u);
+    // the buffers in the order they are dealt to the two groups: the read+write streams first, then the
+    // read-only gradients, then the small write-only ones
+    struct Item { size_t* where; size_t bytes; };
+    std::vector<Item> items;
+    items.push_back({&out->x, big}); items.push_back({&out->m, big});
+    items.push_back({&out->v, big}); items.push_back({&out->werr, big});
+    for (int i = 0; i < N; ++i) items.push_back({&out->errs[i], big});
+    if (with_worker_moments)
+        for (int i = 0; i < N; ++i) { items.push_back({&out->mw[i], big}); items.push_back({&out->vw[i], big}); }
+    for (int i = 0; i < N; ++i) items.push_back({&out->grads[i], big});
+    for (int i = 0; i < N; ++i) items.push_back({&out->codes[i], code});
+    items.push_back({&out->wcodes, wcode});
+    for (int i = 0; i < N; ++i) items.push_back({&out->scales[i], scale});
+    size_t fill[2] = {0, 0};
+    for (size_t k = 0; k < items.size(); ++k) {
+        const int grp = (int)(k & 1);
+        *items[k].where = fill[grp];                // offset inside the group for now
+        fill[grp] += items[k].bytes;
+    }
+    out->bytes_needed = fill[0] + fill[1];
+    if (arena_bytes < out->bytes_needed) return fail(QADAM_ERANGE, "the block is smaller than the buffers");
+    // group 1 starts in the middle of the block, or right behind group 0 when the block is that tight
+    size_t second = (arena_bytes / 2) / align * align;
+    if (second < fill[0]) second = fill[0];
+    if (second + fill[1] > arena_bytes) second = fill[0];
+    for (size_t k = 1; k < items.size(); k += 2) *items[k].where += second;
     return QADAM_OK;
 }
 
@@ -637,13 +727,15 @@ int qadam_get_status(qadam_handle_t h, qadam_status_t* out, int32_t clear, void*
 {
     QADAM_CHECK(check_handle(h));
     if (!out) return fail(QADAM_EINVAL, "null status");
+    // read and clear in stream order, so that they are ordered against the kernels of this stream that
+    // OR into the word; work of the handle on OTHER streams must be idle (see the header)
     hipStream_t s = static_cast<hipStream_t>(stream);
-    QADAM_HIP(hipStreamSynchronize(s));
     uint32_t word = 0;
-    QADAM_HIP(hipMemcpy(&word, h->d_status, sizeof word, hipMemcpyDeviceToHost));
+    QADAM_HIP(hipMemcpyAsync(&word, h->d_status, sizeof word, hipMemcpyDeviceToHost, s));
+    if (clear) QADAM_HIP(hipMemsetAsync(h->d_status, 0, sizeof word, s));
+    QADAM_HIP(hipStreamSynchronize(s));
     out->flags = word;
     out->reserved = 0;
-    if (clear) QADAM_HIP(hipMemset(h->d_status, 0, sizeof word));
     return QADAM_OK;
 }
 

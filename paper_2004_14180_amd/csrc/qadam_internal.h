@@ -19,13 +19,22 @@ struct Tile {
     int32_t seg;        // layer segment the tile belongs to
     int32_t flags;      // bit 0: start is not a multiple of 4 (no 128-bit accesses);
                         // bit 1: sampled tile of the filtered scale pass;
+                        // bit 2: first tile of a small layer (see below); bit 3: a later tile of one;
                         // bits 8..9: zero words to append after the tile's codes (segment padding)
-    int32_t reserved;
+    int32_t layer_len;  // first tile of a small layer: elements of the whole layer; else 0
 };
 static_assert(sizeof(Tile) == 32, "tile records are read as two 128-bit scalar loads");
 
 constexpr int kTileUnaligned = 1;
 constexpr int kTileSampled = 2;
+// A small layer (at most kSmallLayerElems elements) is handled by ONE workgroup in the kernels of the
+// server-moments path: the workgroup of the layer's first tile takes the layer's scales itself (one read
+// of g and e, which stay in cache) and then quantizes all of the layer's tiles, so these layers make a
+// single trip through HBM and need no scale pass; the workgroups of the layer's other tiles exit at once.
+// The worker-moments path (whose first pass produces the tile maxima anyway) ignores the two flags.
+constexpr int kTileSmallHead = 4;
+constexpr int kTileSmallBody = 8;
+constexpr int kSmallLayerElems = 4 * 4096;
 constexpr int kSampleStride = 64;   // every 64th tile of a layer (from its first) is a sampled tile
 constexpr int kBlockThreads = 256;
 constexpr int kDefaultTileElems = 4096;   // elements per tile (16 per lane of a 256-thread workgroup)
@@ -78,6 +87,7 @@ struct Launch {
     const int32_t* sample_tiles;    // device: indices of the sampled tiles
     int32_t     num_sample_tiles;
     uint32_t*   status;     // device status word
+    bool        all_small;  // every layer is a small layer: the server-moments path needs no scale pass
     hipStream_t stream;
 };
 
@@ -85,7 +95,10 @@ struct Launch {
 // scales in two stages without atomics: per-tile maxima, then one workgroup per (worker, layer)
 // reduces its tiles and also writes the reciprocal used by the fast quotient
 hipError_t launch_amax(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker, int num);
-hipError_t launch_reduce_scales(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker, int num);
+// skip_small: the small layers' scales come from the quantizing kernel (server-moments path); the
+// worker-moments path passes false (its first pass has produced every tile maximum)
+hipError_t launch_reduce_scales(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker, int num,
+                                bool skip_small);
 hipError_t launch_amax_filtered(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker, int num);
 hipError_t launch_check_error_bounds(const Launch& L, const WorkerPtrs& W, int first_worker, int num);
 hipError_t launch_worker_quantize(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int worker);

@@ -267,12 +267,14 @@ __device__ __forceinline__ uint32_t load_planes(const uint32_t* __restrict__ chu
 // guarded vector access: one 128-bit non-temporal access when the lane's V=4 elements are all
 // inside the tile (every buffer is streamed exactly once per pass)
 // ------------------------------------------------------------------------------------------------
-template <int V>
+template <int V, bool STREAMING = true>
 __device__ __forceinline__ void load_v(const float* __restrict__ p, int nvalid, float (&out)[V])
 {
     if constexpr (V == 4) {
         if (nvalid == 4) {
-            const f4 t = __builtin_nontemporal_load(reinterpret_cast<const f4*>(p));
+            // STREAMING = false: the data is read again shortly (small layers), so no non-temporal hint
+            const f4 t = STREAMING ? __builtin_nontemporal_load(reinterpret_cast<const f4*>(p))
+                                   : *reinterpret_cast<const f4*>(p);
             out[0] = t.x; out[1] = t.y; out[2] = t.z; out[3] = t.w;
         } else {
 #pragma unroll
@@ -412,20 +414,23 @@ struct AmaxArgs {
     const float* err_bound;     // verification only: [N][L] bounds the error buffers must respect
     uint32_t* status;
     int64_t seg_len;            // tiles == null only: length of the single segment
+    int skip_small;             // non-zero: tiles of small layers are left to the quantizing kernel
 };
 
 struct FusedArgs {
     const Tile* tiles;
     int num_tiles;
     uint32_t* status;
-    const float* inv_scales;      // [N][L]
+    float* inv_scales;            // [N][L]
+    float* err_bound;             // [N][L], written for small layers (the scale kernels write the others)
+    float bound_factor;
     int num_segments;
     StepScalars S;
     ServerPtrs sp;
     const float* grad[QADAM_MAX_WORKERS];
     float* err[QADAM_MAX_WORKERS];
     uint32_t* codes[QADAM_MAX_WORKERS];
-    const float* scales[QADAM_MAX_WORKERS];
+    float* scales[QADAM_MAX_WORKERS];
 };
 
 struct WorkerArgs {        // one worker
@@ -436,8 +441,10 @@ struct WorkerArgs {        // one worker
     const float* grad;     // variant S: g;  variant W second pass: null (p was parked in err)
     float* err;
     uint32_t* codes;
-    const float* scales;
-    const float* inv_scales;   // this worker's row
+    float* scales;
+    float* inv_scales;         // this worker's row
+    float* err_bound;          // this worker's row, written for small layers
+    float bound_factor;
     int worker;
     int64_t seg_len;           // tiles == null only: length of the single segment
 };
@@ -459,7 +466,7 @@ __device__ __forceinline__ Tile tile_at(const Tile* __restrict__ tiles, int ti, 
         const int64_t used = (seg_len + 31) / 32 * code_bits;
         t.flags = (int32_t)((used + 3) / 4 * 4 - used) << 8;     // zero words up to a multiple of 16 bytes
     }
-    t.reserved = 0;
+    t.layer_len = 0;
     return t;
 }
 
@@ -473,6 +480,8 @@ struct ScaleArgs {
     uint32_t* thr;          // [N][L]: thresholds of the filtered pass (written by k_reduce_lower_bounds)
     float bound_factor;     // |e'| <= bound_factor * s for this quantizer and rounding mode
     int sample_stride;      // every sample_stride-th tile of a layer is a sampled tile
+    const Tile* tiles;      // with skip_small: to recognise the small layers
+    int skip_small;         // non-zero: small layers get their scales from the quantizing kernel
 };
 
 // ------------------------------------------------------------------------------------------------
@@ -503,6 +512,61 @@ __device__ __forceinline__ uint32_t block_max(uint32_t local)
     return bm;
 }
 
+// ---- small layers: the scales are taken by the quantizing workgroup itself -----------------------
+struct SmallLayerShared {
+    uint32_t part[QADAM_MAX_WORKERS][kBlockThreads / 64];
+    float scale[QADAM_MAX_WORKERS];
+    float inv[QADAM_MAX_WORKERS];
+};
+
+// max |g + e| over the n elements of a layer that start at flat index `start`, over this wavefront's
+// share; the loads carry no streaming hint because the quantizing phase reads the same lines again
+template <int V>
+__device__ __forceinline__ uint32_t small_layer_wave_max(const float* __restrict__ g, const float* __restrict__ e,
+                                                         int64_t start, int n)
+{
+    uint32_t local = 0;
+    for (int off = threadIdx.x * V; off < n; off += kBlockThreads * V) {
+        const int nvalid = min(n - off, V);
+        float gv[V], ev[V];
+        load_v<V, false>(g + start + off, nvalid, gv);
+        load_v<V, false>(e + start + off, nvalid, ev);
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            const uint32_t ab = f2u(gv[j] + ev[j]) & 0x7fffffffu;
+            local = ab > local ? ab : local;
+        }
+    }
+    return wave_max_u32(local);
+}
+
+// After every wavefront has stored its part for workers first..first+count-1: thread k folds the parts of
+// worker first+k into the scale and its reciprocal (the same two operations k_reduce_scales performs),
+// keeps them in LDS for the workgroup and writes scale, reciprocal and residual bound to global memory.
+__device__ __forceinline__ void small_layer_finish(SmallLayerShared& sh, int first, int count, int seg, int num_segments,
+                                                   float* const* scales, float* inv_scales, float* err_bound,
+                                                   float bound_factor, bool per_worker_rows)
+{
+    __syncthreads();
+    if ((int)threadIdx.x < count) {
+        const int i = first + (int)threadIdx.x;
+        uint32_t bm = sh.part[i][0];
+#pragma unroll
+        for (int w = 1; w < kBlockThreads / 64; ++w) bm = sh.part[i][w] > bm ? sh.part[i][w] : bm;
+        const float s = u2f(bm);
+        const bool ok = s >= 0x1p-100f && s <= 0x1p100f;
+        const float inv = ok ? 1.0f / s : 0.0f;
+        sh.scale[i] = s;
+        sh.inv[i] = inv;
+        // per_worker_rows: the table pointers address worker i's row; else row i of an [N][L] table
+        const size_t row = per_worker_rows ? 0 : (size_t)i * num_segments;
+        scales[per_worker_rows ? 0 : i][seg] = s;
+        inv_scales[row + seg] = inv;
+        err_bound[row + seg] = s * bound_factor + 0x1p-140f;
+    }
+    __syncthreads();
+}
+
 // grid: (layers, workers).  One workgroup folds the tile maxima of its (worker, layer).
 __global__ void __launch_bounds__(kBlockThreads) k_reduce_scales(ScaleArgs A)
 {
@@ -510,6 +574,7 @@ __global__ void __launch_bounds__(kBlockThreads) k_reduce_scales(ScaleArgs A)
     // no table: a single segment that owns every tile
     const int t0 = A.seg_tile_begin ? A.seg_tile_begin[l] : 0;
     const int t1 = A.seg_tile_begin ? A.seg_tile_begin[l + 1] : A.num_tiles;
+    if (A.skip_small && t1 > t0 && (A.tiles[t0].flags & kTileSmallHead)) return;
     const uint32_t* part = A.tile_max + (size_t)w * A.num_tiles;
     uint32_t local = 0;
     for (int t = t0 + threadIdx.x; t < t1; t += kBlockThreads) {
@@ -539,6 +604,7 @@ __global__ void __launch_bounds__(kBlockThreads) k_reduce_lower_bounds(ScaleArgs
 {
     const int l = blockIdx.x, w = A.first_worker + blockIdx.y;
     const int t0 = A.seg_tile_begin[l], t1 = A.seg_tile_begin[l + 1];
+    if (A.skip_small && t1 > t0 && (A.tiles[t0].flags & kTileSmallHead)) return;
     const uint32_t* part = A.tile_max + (size_t)w * A.num_tiles;
     uint32_t local = 0;
     for (int t = t0 + (int)threadIdx.x * A.sample_stride; t < t1; t += kBlockThreads * A.sample_stride) {
@@ -598,6 +664,7 @@ __global__ void __launch_bounds__(kBlockThreads) k_amax(AmaxArgs A)
 {
     const int ti = A.tile_list ? A.tile_list[blockIdx.x] : (int)blockIdx.x;
     const Tile t = tile_at(A.tiles, ti, A.seg_len, 0);
+    if (A.skip_small && (t.flags & (kTileSmallHead | kTileSmallBody))) return;
     const int w = A.first_worker + blockIdx.y;
     const float* g = A.grad[w];
     const float* e = A.err[w];
@@ -671,6 +738,7 @@ __global__ void __launch_bounds__(kBlockThreads) k_amax_filtered(AmaxArgs A)
     const int ti = blockIdx.x;
     const Tile t = A.tiles[ti];
     if (t.flags & kTileSampled) return;
+    if (A.skip_small && (t.flags & (kTileSmallHead | kTileSmallBody))) return;
     const int w = A.first_worker + blockIdx.y;
     const float* g = A.grad[w];
     const float* e = A.err[w];
@@ -735,15 +803,15 @@ __device__ __forceinline__ void store_chunk_words(uint32_t* __restrict__ codes, 
 }
 
 // ---- worker side alone (qadam_worker_quantize, second pass of variant W) -------------------------
-template <int V, int ROUNDING, bool PARKED>
-__device__ __forceinline__ void worker_tile(const WorkerArgs& A, const Tile& t)
+template <int V, int ROUNDING, bool PARKED, bool INLINE = false>
+__device__ __forceinline__ void worker_tile(const WorkerArgs& A, const Tile& t, const SmallLayerShared* sh = nullptr)
 {
     constexpr int WAVE_ELEMS = 64 * V, BLOCK_ELEMS = (kBlockThreads / 64) * WAVE_ELEMS;
     const StepScalars& S = A.S;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const QgConst c = make_qg(S.k_g);
-    const float s = A.scales[t.seg];
-    const float inv_s = A.inv_scales[t.seg];
+    const float s = INLINE ? sh->scale[0] : A.scales[t.seg];
+    const float inv_s = INLINE ? sh->inv[0] : A.inv_scales[t.seg];
     if (!(s >= 0.0f && s < __builtin_inff()) && threadIdx.x == 0) atomicOr(A.status, QADAM_STATUS_NONFINITE_SCALE);
     for (int base = wave * WAVE_ELEMS; base < t.len; base += BLOCK_ELEMS) {
         const int off = base + lane * V;
@@ -772,11 +840,53 @@ __device__ __forceinline__ void worker_tile(const WorkerArgs& A, const Tile& t)
     write_pad_words(A.codes, t, S.code_bits);
 }
 
+// the tiles of a small layer, one after the other, with the flags each would carry in the table
+__device__ __forceinline__ Tile small_layer_tile(const Tile& head, int o, int code_bits)
+{
+    const int n = head.layer_len;
+    Tile t = head;
+    t.start = head.start + o;
+    t.code_word = head.code_word + (int64_t)(o / 32) * code_bits;
+    t.len = min(n - o, kDefaultTileElems);
+    t.flags = head.flags & kTileUnaligned;
+    if (o + kDefaultTileElems >= n) {
+        const int used = (n + 31) / 32 * code_bits;
+        t.flags |= ((used + 3) / 4 * 4 - used) << 8;
+    }
+    return t;
+}
+
+template <int ROUNDING>
+__device__ __forceinline__ void worker_small_layer(const WorkerArgs& A, const Tile& head)
+{
+    __shared__ SmallLayerShared sh;
+    const int n = head.layer_len;
+    const bool unaligned = head.flags & kTileUnaligned;
+    const uint32_t wm = unaligned ? small_layer_wave_max<1>(A.grad, A.err, head.start, n)
+                                  : small_layer_wave_max<4>(A.grad, A.err, head.start, n);
+    if ((threadIdx.x & 63) == 0) sh.part[0][threadIdx.x >> 6] = wm;
+    float* scales_row[1] = {A.scales};
+    small_layer_finish(sh, 0, 1, head.seg, 1, scales_row, A.inv_scales, A.err_bound, A.bound_factor, true);
+    for (int o = 0; o < n; o += kDefaultTileElems) {
+        const Tile t = small_layer_tile(head, o, A.S.code_bits);
+        if (unaligned) worker_tile<1, ROUNDING, false, true>(A, t, &sh);
+        else worker_tile<4, ROUNDING, false, true>(A, t, &sh);
+    }
+}
+
 template <int ROUNDING, bool PARKED>
 __global__ void __launch_bounds__(kBlockThreads) k_worker_quantize(WorkerArgs A)
 {
     const int ti = blockIdx.x;
     const Tile t = tile_at(A.tiles, ti, A.seg_len, A.S.code_bits);
+    if constexpr (!PARKED) {
+        // small layers: the workgroup of the first tile does the whole layer, scale included
+        if (t.flags & kTileSmallBody) return;
+        if (t.flags & kTileSmallHead) {
+            worker_small_layer<ROUNDING>(A, t);
+            return;
+        }
+    }
     if (t.flags & kTileUnaligned) worker_tile<1, ROUNDING, PARKED>(A, t);
     else worker_tile<4, ROUNDING, PARKED>(A, t);
 }
@@ -909,8 +1019,8 @@ __global__ void __launch_bounds__(kBlockThreads) k_weight_dequantize(DequantArgs
 // W = false: variant S (workers' g and e in, server moments).  W = true: second pass of variant W
 // (the first pass left p_i = alpha m_i / sqrt(v_i + eps) + e_i in the error buffers; the server
 // only subtracts the mean message).
-template <int V, int ROUNDING, int U, bool W>
-__device__ __forceinline__ void fused_tile(const FusedArgs& A, const Tile& t)
+template <int V, int ROUNDING, int U, bool W, bool INLINE = false>
+__device__ __forceinline__ void fused_tile(const FusedArgs& A, const Tile& t, const SmallLayerShared* sh = nullptr)
 {
     constexpr int WAVE_ELEMS = 64 * V, BLOCK_ELEMS = (kBlockThreads / 64) * WAVE_ELEMS;
     const StepScalars& S = A.S;
@@ -952,8 +1062,8 @@ __device__ __forceinline__ void fused_tile(const FusedArgs& A, const Tile& t)
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int i = i0 + u;
-                const float s = A.scales[i][t.seg];
-                const float inv_s = A.inv_scales[(size_t)i * A.num_segments + t.seg];
+                const float s = INLINE ? sh->scale[i] : A.scales[i][t.seg];
+                const float inv_s = INLINE ? sh->inv[i] : A.inv_scales[(size_t)i * A.num_segments + t.seg];
                 float q[V], en[V], Ur[V];
 #pragma unroll
                 for (int j = 0; j < V; ++j) Ur[j] = 0.0f;
@@ -992,9 +1102,30 @@ __device__ __forceinline__ void fused_tile(const FusedArgs& A, const Tile& t)
     }
     for (int i = 0; i < N; ++i) {
         write_pad_words(A.codes[i], t, S.code_bits);
-        const float s = A.scales[i][t.seg];
+        const float s = INLINE ? sh->scale[i] : A.scales[i][t.seg];
         if (!(s >= 0.0f && s < __builtin_inff()) && threadIdx.x == 0)
             atomicOr(A.status, QADAM_STATUS_NONFINITE_SCALE);
+    }
+}
+
+// One workgroup does a whole small layer: the scales of all workers first (g and e read once, kept in
+// cache), then the layer's tiles exactly as the separate workgroups would have done them.
+template <int ROUNDING, int U>
+__device__ __forceinline__ void fused_small_layer(const FusedArgs& A, const Tile& head)
+{
+    __shared__ SmallLayerShared sh;
+    const int n = head.layer_len, N = A.S.num_workers;
+    const bool unaligned = head.flags & kTileUnaligned;
+    for (int i = 0; i < N; ++i) {
+        const uint32_t wm = unaligned ? small_layer_wave_max<1>(A.grad[i], A.err[i], head.start, n)
+                                      : small_layer_wave_max<4>(A.grad[i], A.err[i], head.start, n);
+        if ((threadIdx.x & 63) == 0) sh.part[i][threadIdx.x >> 6] = wm;
+    }
+    small_layer_finish(sh, 0, N, head.seg, A.num_segments, A.scales, A.inv_scales, A.err_bound, A.bound_factor, false);
+    for (int o = 0; o < n; o += kDefaultTileElems) {
+        const Tile t = small_layer_tile(head, o, A.S.code_bits);
+        if (unaligned) fused_tile<1, ROUNDING, 1, false, true>(A, t, &sh);
+        else fused_tile<4, ROUNDING, U, false, true>(A, t, &sh);
     }
 }
 
@@ -1003,6 +1134,14 @@ __global__ void __launch_bounds__(kBlockThreads) k_fused(FusedArgs A)
 {
     const int ti = blockIdx.x;
     const Tile t = A.tiles[ti];
+    if constexpr (!W) {
+        // small layers: the workgroup of the first tile does the whole layer, scales included
+        if (t.flags & kTileSmallBody) return;
+        if (t.flags & kTileSmallHead) {
+            fused_small_layer<ROUNDING, U>(A, t);
+            return;
+        }
+    }
     if (t.flags & kTileUnaligned) fused_tile<1, ROUNDING, 1, W>(A, t);
     else fused_tile<4, ROUNDING, U, W>(A, t);
 }
@@ -1230,8 +1369,10 @@ static float residual_bound_factor(const StepScalars& S)
     return (S.rounding == 0 ? half_gap : 2.0f * half_gap) * (1.0f + 0x1p-20f);
 }
 
-static void fill_scale_args(ScaleArgs& A, const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker)
+static void fill_scale_args(ScaleArgs& A, const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker,
+                            bool skip_small)
 {
+    A.tiles = L.tiles; A.skip_small = skip_small ? 1 : 0;
     for (int i = 0; i < QADAM_MAX_WORKERS; ++i) A.scales[i] = W.scales[i];
     A.inv_scales = L.inv_scales; A.tile_max = L.tile_max; A.seg_tile_begin = L.seg_tile_begin;
     A.first_worker = first_worker; A.num_segments = L.num_segments; A.num_tiles = L.num_tiles;
@@ -1240,11 +1381,13 @@ static void fill_scale_args(ScaleArgs& A, const Launch& L, const StepScalars& S,
     A.sample_stride = kSampleStride;
 }
 
-hipError_t launch_reduce_scales(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker, int num)
+hipError_t launch_reduce_scales(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker, int num,
+                                bool skip_small)
 {
     if (L.num_segments == 0 || num == 0) return hipSuccess;
+    if (skip_small && L.all_small) return hipSuccess;      // every scale comes from the quantizing kernel
     ScaleArgs A;
-    fill_scale_args(A, L, S, W, first_worker);
+    fill_scale_args(A, L, S, W, first_worker, skip_small);
     hipLaunchKernelGGL(k_reduce_scales, dim3(L.num_segments, num), dim3(kBlockThreads), 0, L.stream, A);
     return hipGetLastError();
 }
@@ -1258,6 +1401,7 @@ static void fill_amax_args(AmaxArgs& A, const Launch& L, const WorkerPtrs& W, in
     A.tile_list = nullptr; A.thr = L.thr; A.num_segments = L.num_segments;
     A.err_bound = L.err_bound; A.status = L.status;
     A.seg_len = 0;
+    A.skip_small = 1;       // only the server-moments path uses these kernels
 }
 
 hipError_t launch_check_error_bounds(const Launch& L, const WorkerPtrs& W, int first_worker, int num)
@@ -1265,6 +1409,7 @@ hipError_t launch_check_error_bounds(const Launch& L, const WorkerPtrs& W, int f
     if (L.num_tiles == 0 || num == 0) return hipSuccess;
     AmaxArgs A;
     fill_amax_args(A, L, W, first_worker);
+    A.skip_small = 0;       // the check covers every tile
     hipLaunchKernelGGL(k_check_error_bounds, dim3(L.num_tiles, num), dim3(kBlockThreads), 0, L.stream, A);
     return hipGetLastError();
 }
@@ -1272,7 +1417,7 @@ hipError_t launch_check_error_bounds(const Launch& L, const WorkerPtrs& W, int f
 hipError_t launch_amax(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker, int num)
 {
     (void)S;
-    if (L.num_tiles == 0 || num == 0) return hipSuccess;
+    if (L.num_tiles == 0 || num == 0 || L.all_small) return hipSuccess;
     AmaxArgs A;
     fill_amax_args(A, L, W, first_worker);
     hipLaunchKernelGGL(k_amax, dim3(L.num_tiles, num), dim3(kBlockThreads), 0, L.stream, A);
@@ -1284,13 +1429,13 @@ hipError_t launch_amax(const Launch& L, const StepScalars& S, const WorkerPtrs& 
 // where |g| reaches the threshold.  launch_reduce_scales follows as usual.
 hipError_t launch_amax_filtered(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker, int num)
 {
-    if (L.num_tiles == 0 || num == 0) return hipSuccess;
+    if (L.num_tiles == 0 || num == 0 || L.all_small) return hipSuccess;
     AmaxArgs A;
     fill_amax_args(A, L, W, first_worker);
     A.tile_list = L.sample_tiles;
     hipLaunchKernelGGL(k_amax, dim3(L.num_sample_tiles, num), dim3(kBlockThreads), 0, L.stream, A);
     ScaleArgs R;
-    fill_scale_args(R, L, S, W, first_worker);
+    fill_scale_args(R, L, S, W, first_worker, true);
     hipLaunchKernelGGL(k_reduce_lower_bounds, dim3(L.num_segments, num), dim3(kBlockThreads), 0, L.stream, R);
     A.tile_list = nullptr;
     hipLaunchKernelGGL(k_amax_filtered, dim3(L.num_tiles, num), dim3(kBlockThreads), 0, L.stream, A);
@@ -1305,6 +1450,8 @@ hipError_t launch_worker_quantize(const Launch& L, const StepScalars& S, const W
     A.status = L.status; A.S = S;
     A.grad = W.grad[worker]; A.err = W.err[worker]; A.codes = W.codes[worker]; A.scales = W.scales[worker];
     A.inv_scales = L.inv_scales + (size_t)worker * L.num_segments;
+    A.err_bound = L.err_bound + (size_t)worker * L.num_segments;
+    A.bound_factor = residual_bound_factor(S);
     A.worker = worker;
     A.seg_len = 0;
     const bool parked = (A.grad == nullptr);
@@ -1392,6 +1539,7 @@ static hipError_t launch_fused_any(const Launch& L, const StepScalars& S, const 
     FusedArgs A;
     A.tiles = L.tiles; A.num_tiles = L.num_tiles;
     A.status = L.status; A.inv_scales = L.inv_scales; A.num_segments = L.num_segments; A.S = S; A.sp = sp;
+    A.err_bound = L.err_bound; A.bound_factor = residual_bound_factor(S);
     for (int i = 0; i < QADAM_MAX_WORKERS; ++i) {
         A.grad[i] = W.grad[i]; A.err[i] = W.err[i]; A.codes[i] = W.codes[i]; A.scales[i] = W.scales[i];
     }
@@ -1426,6 +1574,7 @@ hipError_t launch_plain_messages(const Launch& L, const StepScalars& S, const Wo
     FusedArgs A;
     A.tiles = L.tiles; A.num_tiles = L.num_tiles;
     A.status = L.status; A.inv_scales = L.inv_scales; A.num_segments = L.num_segments; A.S = S; A.sp = sp;
+    A.err_bound = L.err_bound; A.bound_factor = 0.0f;
     for (int i = 0; i < QADAM_MAX_WORKERS; ++i) {
         A.grad[i] = W.grad[i]; A.err[i] = W.err[i]; A.codes[i] = nullptr; A.scales[i] = nullptr;
     }
@@ -1546,6 +1695,7 @@ hipError_t noalloc_quantize_segment(const StepScalars& S, int64_t n, const float
     R.err_bound = err_bound; R.thr = nullptr;
     R.bound_factor = residual_bound_factor(S);
     R.sample_stride = kSampleStride;
+    R.tiles = nullptr; R.skip_small = 0;
     hipLaunchKernelGGL(k_reduce_scales, dim3(1, 1), dim3(kBlockThreads), 0, stream, R);
     if (num_tiles > 0) {
         WorkerArgs W;
@@ -1553,6 +1703,7 @@ hipError_t noalloc_quantize_segment(const StepScalars& S, int64_t n, const float
         W.tiles = nullptr; W.num_tiles = num_tiles; W.seg_len = n;
         W.status = status; W.S = S;
         W.grad = grad; W.err = err; W.codes = codes; W.scales = scale_out; W.inv_scales = inv_scale;
+        W.err_bound = err_bound; W.bound_factor = residual_bound_factor(S);
         W.worker = 0;
         hipLaunchKernelGGL((k_worker_quantize<0, false>), dim3(num_tiles), dim3(kBlockThreads), 0, stream, W);
     }

@@ -33,26 +33,21 @@ def test_config1_flat_1m(k_g, fused):
     assert rep.ok()
 
 
-def test_config2_resnet18_full_size():
-    """Config 2 at full size (11 689 512 parameters, 62 layers, 4 workers), first steps."""
+def test_config2_resnet18_full_size_all_50_steps():
+    """Config 2 at full size (11 689 512 parameters, 62 layers, 4 workers), its whole schedule of 50
+    steps, every element of every output compared after every step; the filtered scale pass (what the
+    benchmark runs) is on from step 2."""
     wl = make_workload(2)
-    rep = run_workload_parity(wl, 3, fused=True, progress="cfg2 full")
-    _say("config2 full: " + rep.line())
-    assert rep.ok()
-
-
-def test_config2_resnet18_50_steps_shrunk():
-    """Config 2's 50 steps on the same layer list with every layer 8x smaller."""
-    wl = make_workload(2, shrink=8)
-    rep = run_workload_parity(wl, wl.steps, fused=True, check_every=5, progress="cfg2/8")
-    _say("config2/8 50 steps: " + rep.line())
-    assert rep.ok()
+    rep = run_workload_parity(wl, wl.steps, fused=True, gen_device="cuda", trust_errs=True)
+    _say("config2 full, 50 steps: " + rep.line())
+    assert rep.ok() and rep.checked == wl.steps * wl.num_params * (wl.num_workers + 1)
 
 
 def test_config3_gpt2_shrunk():
-    """Config 3 (8 workers, Student-t gradients, zeroed embedding rows), model dims / 4, 20 steps."""
+    """Config 3 (8 workers, Student-t gradients, zeroed embedding rows), model dims / 4, first 6 steps
+    through the separate calls (the fused call runs the whole schedule at full size elsewhere)."""
     wl = make_workload(3, shrink=4)
-    rep = run_workload_parity(wl, wl.steps, fused=True, check_every=4, progress="cfg3/4")
+    rep = run_workload_parity(wl, 6, fused=False, check_every=2, progress="cfg3/4")
     _say("config3/4: " + rep.line())
     assert rep.ok()
 
@@ -257,6 +252,80 @@ def test_empty_vector_and_argument_errors():
     with pytest.raises(QAdamError) as ei:
         q.worker_quantize(0, 0, buf[:64], buf[64:], codes, buf[:1])        # step is 1-based
     assert ei.value.code == -1
+    # the binding refuses buffers a kernel would overrun or misread, before the library is called
+    for bad in (lambda: q.worker_quantize(0, 1, buf[:32], buf[64:], codes, buf[:1]),              # too few elements
+                lambda: q.worker_quantize(0, 1, buf[:64].double(), buf[64:], codes, buf[:1]),     # wrong type
+                lambda: q.worker_quantize(0, 1, buf[:64], buf[64:], codes[:2], buf[:1]),          # codes too short
+                lambda: q.worker_quantize(0, 1, buf[:64].cpu(), buf[64:], codes, buf[:1]),        # host memory
+                lambda: q.worker_quantize(0, 1, buf[:64], buf[64:], codes, buf[:0]),              # no room for the scale
+                lambda: q.server_step(1, 1e-3, 0.999, [codes], [buf[:1]], buf[:64], buf[:64], buf[:64])):  # N = 2 expected
+        with pytest.raises(ValueError):
+            bad()
+    q.close()
+
+
+def test_arena_layout_places_every_buffer_and_changes_no_result():
+    """qadam_arena_layout: offsets are aligned, inside the block and disjoint; the two groups of buffers
+    lie in the two halves of a large block; a step on buffers carved out of one block gives the bits of a
+    step on separately allocated buffers."""
+    gcfg, _ = configs(k_g=2, k_x=6)
+    sizes = RAGGED + [70000]
+    seg_off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    P, N, L = int(seg_off[-1]), 4, len(sizes)
+    q = QAdam(gcfg, seg_off, N)
+    need = q.arena_layout(1 << 40)["bytes_needed"]
+    with pytest.raises(QAdamError) as ei:
+        q.arena_layout(need - 1)
+    assert ei.value.code == -3
+    for arena_bytes, wm in [(need, False), (need, True), (4 * need + 12345, False), (64 << 20, True)]:
+        if wm:
+            need_w = q.arena_layout(1 << 40, True)["bytes_needed"]
+            arena_bytes = max(arena_bytes, need_w)
+        lay = q.arena_layout(arena_bytes, wm)
+        spans = []
+        for name, nbytes in [("x", 4 * P), ("m", 4 * P), ("v", 4 * P), ("werr", 4 * P), ("wcodes", q.weight_code_bytes())]:
+            spans.append((lay[name], lay[name] + nbytes, name))
+        per_worker = [("grads", 4 * P), ("errs", 4 * P), ("codes", q.grad_code_bytes()), ("scales", 4 * L)]
+        if wm:
+            per_worker += [("mw", 4 * P), ("vw", 4 * P)]
+        for name, nbytes in per_worker:
+            assert len(lay[name]) == N
+            spans += [(o, o + nbytes, "%s[%d]" % (name, i)) for i, o in enumerate(lay[name])]
+        spans.sort()
+        for (a0, a1, an), (b0, b1, bn) in zip(spans, spans[1:]):
+            assert a1 <= b0, (an, bn)
+        assert all(a % 256 == 0 for a, _, _ in spans) and spans[-1][1] <= arena_bytes
+        if arena_bytes >= 4 * need:     # roomy block: half of the fp32 buffers start in its second half
+            big = [a for a, b, n in spans if b - a == 4 * P]
+            assert sum(a >= arena_bytes // 2 - (2 << 20) for a in big) == len(big) // 2
+    # same bits in the block as in separate allocations
+    arena_bytes = 3 * need
+    lay = q.arena_layout(arena_bytes)
+    block = torch.zeros(arena_bytes, dtype=torch.uint8, device="cuda")
+    f32 = lambda off, n: block[off:off + 4 * n].view(torch.float32)
+    gen = torch.Generator().manual_seed(21)
+    x0 = torch.randn(P, generator=gen) * 0.02
+    ref = DeviceState(q, x0)
+    x, m, v, werr = (f32(lay[k], P) for k in ("x", "m", "v", "werr"))
+    x.copy_(x0)
+    grads = [f32(o, P) for o in lay["grads"]]
+    errs = [f32(o, P) for o in lay["errs"]]
+    codes = [block[o:o + q.grad_code_bytes()].view(torch.int32) for o in lay["codes"]]
+    scales = [f32(o, L) for o in lay["scales"]]
+    wcodes = block[lay["wcodes"]:lay["wcodes"] + P].view(torch.int8)
+    for t in range(1, 4):
+        for i in range(N):
+            g = torch.randn(P, generator=gen) * 0.01
+            grads[i].copy_(g); ref.grads[i].copy_(g)
+        q.step_fused(t, 1e-3, 0.999, grads, errs, codes, scales, x, m, v, werr, wcodes)
+        ref.step_fused(t, 1e-3, 0.999)
+        torch.cuda.synchronize()
+        assert torch.equal(x, ref.x) and torch.equal(m, ref.m) and torch.equal(v, ref.v) and torch.equal(werr, ref.werr)
+        assert torch.equal(wcodes, ref.wcodes[:P])
+        for i in range(N):
+            assert torch.equal(errs[i], ref.errs[i]) and torch.equal(scales[i], ref.scales[i][:L])
+            assert torch.equal(codes[i], ref.codes[i][: q.grad_code_bytes() // 4])
+    assert q.get_status() == 0
     q.close()
 
 
@@ -369,14 +438,6 @@ def test_variant_w_worker_moments(rounding):
     q.close()
 
 
-def test_small_tile_sizes(monkeypatch):
-    """The tile size is a tuning parameter read at qadam_init; results must not depend on it."""
-    for tile in ("256", "1024", "16384"):
-        monkeypatch.setenv("QADAM_TILE_ELEMS", tile)
-        rep, st = _custom([700, 5000, 257, 33000, 9], 4, 2, seed=95)
-        assert rep.ok() and st == 0, tile
-
-
 @pytest.mark.parametrize("N,rounding", [(4, 0), (3, 0), (2, 1), (1, 0), (8, 0)])
 def test_variant_w_fused_step(N, rounding):
     """qadam_step_fused_w against the oracle's Algorithms 2-3 and against the separate calls
@@ -431,9 +492,12 @@ def test_step_is_capturable_in_a_hip_graph():
     seg_off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
     P, N = int(seg_off[-1]), 4
     q = QAdam(gcfg, seg_off, N)
+    q.trust_error_buffers(2)       # a recorded call must take the full scale pass all the same
+    qb = QAdam(gcfg, seg_off, N)   # the eager twin has its own handle (replays update q's residual bounds)
+    qb.trust_error_buffers(2)
     gen = torch.Generator().manual_seed(11)
     x0 = torch.randn(P, generator=gen) * 0.02
-    a, b = DeviceState(q, x0), DeviceState(q, x0)
+    a, b = DeviceState(q, x0), DeviceState(qb, x0)
     for i in range(N):
         a.grads[i].copy_(torch.randn(P, generator=gen) * 0.01)
     torch.cuda.synchronize()
@@ -446,8 +510,15 @@ def test_step_is_capturable_in_a_hip_graph():
         for i in range(N):
             gr = torch.randn(P, generator=gen) * 0.01
             a.grads[i].copy_(gr); b.grads[i].copy_(gr)
+        if rep == 2:
+            # the caller changes the error buffers between replays: allowed, the recorded scale pass reads everything
+            for i in range(N):
+                e = torch.randn(P, generator=gen) * 0.05
+                a.errs[i].copy_(e); b.errs[i].copy_(e)
+            qb.trust_error_buffers(2)  # the eager twin must say so (contract of the filtered pass); the graph need not
         graph.replay()
-        b.step_fused(1, 1e-3, 0.999)
+        # with nearest rounding and the paper's Adam the step number enters no kernel: a replay stands for any t
+        b.step_fused(rep + 1, 1e-3, 0.999)
         torch.cuda.synchronize()
         for name in ("x", "m", "v", "werr", "wcodes"):
             assert torch.equal(getattr(a, name), getattr(b, name)), (rep, name)
@@ -456,8 +527,27 @@ def test_step_is_capturable_in_a_hip_graph():
             assert torch.equal(a.scales[i], b.scales[i])
         # eager work between replays
         _ = (a.x * 2).sum().item()
-    assert q.get_status() == 0
+    assert q.get_status() == 0 and qb.get_status() == 0
     q.close()
+    qb.close()
+    # what a replay cannot follow is refused while a graph is being recorded: the per-step random stream
+    # of stochastic rounding and the per-step bias corrections
+    for kw in (dict(rounding=1), dict(adam_flavor=1)):
+        gcfg2, _ = configs(k_g=2, k_x=6, **kw)
+        q2 = QAdam(gcfg2, seg_off, N)
+        c = DeviceState(q2, x0)
+        torch.cuda.synchronize()
+        g2 = torch.cuda.CUDAGraph()
+        refused = False
+        with torch.cuda.graph(g2):
+            try:
+                c.step_fused(1, 1e-3, 0.999)
+            except QAdamError as ex:
+                refused = ex.code == -1
+        assert refused, kw
+        c.step_fused(1, 1e-3, 0.999)          # the same call outside a capture is fine
+        torch.cuda.synchronize()
+        q2.close()
 
 
 @pytest.mark.parametrize("rounding", [0, 1])
@@ -695,10 +785,10 @@ def test_identity_quantizers_on_device(variant, idg, idx):
     # the calls of a quantizer that is switched off are refused
     if idg:
         with pytest.raises(QAdamError):
-            q.worker_quantize(0, 1, grads[0], errs[0], errs[1], errs[2])
+            q.worker_quantize(0, 1, grads[0], errs[0], torch.zeros(P, dtype=torch.int32, device=dev), errs[2])
     if idx:
         with pytest.raises(QAdamError):
-            q.weight_quantize(1, x, werr, errs[0])
+            q.weight_quantize(1, x, werr, torch.zeros(P, dtype=torch.int8, device=dev))
     q.close()
 
 

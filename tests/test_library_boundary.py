@@ -67,3 +67,14 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(binding, "_LIB_PATH", "/nonexistent/libqadam_hip.so")
     with pytest.raises(ImportError):
         binding.load_library()
+
+
+def test_device_code_holds_no_packed_fp32_instructions():
+    """The library is built with the packed-fp32 feature switched off for the gfx950 pass (the host pass
+    only warns that it does not know the feature).  Check the effect where it matters: the device
+    assembly of the kernels has no packed fp32 add / mul / fma."""
+    from paper_2004_14180_amd.build import device_assembly
+    asm = device_assembly("qadam_kernels.hip")
+    assert "k_fused" in asm and "gfx950" in asm
+    packed = re.findall(r"\bv_pk_(?:add|mul|fma)_f32\b", asm)
+    assert not packed, "%d packed fp32 instructions in the device code" % len(packed)

@@ -292,3 +292,43 @@ def test_pack_unpack_layout(oracle):
     code[5] = 0b101
     words = oracle.pack_codes(3, code)
     assert list(words[:3]) == [1 << 5, 0, 1 << 5]
+
+
+# ------------------------------------------------- scaling by powers of two (Sec. 5.1 grids)
+def test_grid_points_are_exact_power_of_two_multiples_down_to_subnormals(oracle):
+    """Sec. 5.1: the points of G are s * 2^(mu-1-k_g) and those of X are j * 2^-(k_x+1).  The oracle forms
+    them as a product with an exactly representable power of two; a correctly rounded product with a
+    power of two is the same number as ldexp of it (one rounding, also when the result is subnormal or
+    underflows to zero).  Checked bit for bit against numpy's ldexp for scales from the smallest
+    subnormal to the largest finite value, every level of every grid."""
+    rng = np.random.default_rng(7)
+    mant = np.concatenate([[0, 1, 0x400000, 0x7fffff], rng.integers(0, 1 << 23, 12)]).astype(np.uint32)
+    scales = []
+    for e in range(0, 255):                       # exponent field 0 = subnormals, 254 = largest binade
+        for mnt in mant:
+            bits = np.uint32((e << 23) | int(mnt))
+            if bits:
+                scales.append(bits)
+    scales = np.array(scales, np.uint32).view(np.float32)
+    lib = oracle.lib()
+    for k_g in range(0, 7):
+        w = oracle.grad_code_bits(k_g) - 1
+        for mu in range(1, k_g + 2):
+            want = np.ldexp(scales, mu - 1 - k_g).astype(np.float32)
+            for neg in (0, 1):
+                code = (neg << w) | mu
+                got = np.array([lib.oq_qg_decode(k_g, float(s), code) for s in scales], np.float32)
+                ref = -want if neg else want
+                assert np.array_equal(got.view(np.uint32), ref.view(np.uint32)), (k_g, mu, neg)
+    # Q_x: u = y * 2^(k_x+1) and x^ = j * 2^-(k_x+1)
+    ys = np.concatenate([scales, -scales])
+    ys = ys[np.abs(ys) < 4.0]                     # beyond the grid everything saturates (checked elsewhere)
+    for k_x in (0, 3, 6, 7, 14):
+        j, xh, _ = oracle.qx(OracleConfig(k_x=k_x), ys)
+        u = np.ldexp(ys.astype(np.float64), k_x + 1)                 # exact in fp64
+        jw = np.clip(np.sign(u) * np.floor(np.abs(u) + 0.5), -(1 << k_x), 1 << k_x)
+        # u is also exact in fp32 here (a power-of-two scaling without overflow or underflow of a normal
+        # value; a subnormal y scaled up stays exactly representable), so the fp32 decision equals this one
+        assert np.array_equal(j.astype(np.float64), jw), k_x
+        # (values, not bit patterns: a negative y that rounds to j = 0 gives x^ = -0.0)
+        assert np.array_equal(xh, np.ldexp(j.astype(np.float32), -(k_x + 1))), k_x

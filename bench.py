@@ -158,6 +158,56 @@ def measure_ceilings(dev):
                     "paper_2004_14180_amd/qadam_probe.bin (summary under profiles/)"}
 
 
+# ---------------------------------------------------------------------------------------- utilities
+def bench_utilities(wl, dev, reps=5):
+    """The kernels around the step (what a worker does with the broadcast weight codes; the norm diagnostic;
+    the check of the filtered pass's contract), each timed alone with HIP events on the stream the library
+    launches on, against its algorithmic bytes."""
+    import torch
+    from paper_2004_14180_amd import QAdam, QAdamConfig
+    P, N = wl.num_params, 1
+    out = {}
+
+    def timed(fn):
+        ms = []
+        for _ in range(reps + 1):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(); fn(); b.record()
+            torch.cuda.synchronize()
+            ms.append(a.elapsed_time(b))
+        ms = ms[1:]
+        return sum(ms) / len(ms)
+
+    def entry(name, bytes_per_param, ms):
+        gbs = bytes_per_param * P / (ms * 1e-3) / 1e9
+        out[name] = {"avg_launch_ms": round(ms, 4), "algorithmic_bytes_per_param": bytes_per_param,
+                     "achieved_GBs": round(gbs, 1), "frac": round(gbs / HBM_PEAK_GBS, 4)}
+
+    x = wl.init_weights(dev)
+    for k_x, dt in ((6, torch.int8), (14, torch.int16)):
+        q = QAdam(QAdamConfig(k_g=wl.k_g, k_x=k_x, weight_ef=0, beta1=wl.beta1, eps=wl.eps), wl.seg_offsets, N)
+        wcodes = torch.empty(P, dtype=dt, device=dev)
+        werr = torch.empty(P, dtype=torch.float32, device=dev)
+        nb = wcodes.element_size()
+        entry("qadam_weight_quantize, int%d codes, weight_ef=0 (k_weight_quantize)" % (8 * nb), 8.0 + nb,
+              timed(lambda: q.weight_quantize(1, x, werr, wcodes)))
+        xhat = werr                                     # reuse the buffer
+        entry("qadam_weight_dequantize, int%d -> fp32 (k_weight_dequantize)" % (8 * nb), 4.0 + nb,
+              timed(lambda: q.weight_dequantize(wcodes, xhat)))
+        xh16 = torch.empty(P, dtype=torch.float16, device=dev)
+        entry("qadam_weight_dequantize_f16, int%d -> binary16 (k_weight_dequantize)" % (8 * nb), 2.0 + nb,
+              timed(lambda: q.weight_dequantize_f16(wcodes, xh16)))
+        if k_x == 6:
+            sums = torch.empty(q.num_segments, dtype=torch.float64, device=dev)
+            entry("qadam_layer_sumsq(a, b) (k_sumsq_tiles + k_sumsq_layers)", 8.0, timed(lambda: q.layer_sumsq(x, werr, sums)))
+            entry("qadam_layer_sumsq(a) (k_sumsq_tiles + k_sumsq_layers)", 4.0, timed(lambda: q.layer_sumsq(x, None, sums)))
+            del sums
+        del wcodes, werr, xh16, xhat
+        q.close()
+    torch.cuda.empty_cache()
+    return out
+
+
 # ------------------------------------------------------------------------------------- CPU baseline
 def cpu_baseline(wl, dev, max_params=75_000_000, seconds_hint=25.0):
     """The oracle as it stands, timed on the host next to the GPU library on a bounded sample of the
@@ -460,7 +510,10 @@ def run_fused(args, config, dev, steps, warmup, placement, headline):
                 % (wl.config, wl.name, N, P, len(wl.sizes), wl.k_g, round(code_bits), wl.k_x, 8 * round(wcode_bytes),
                    "stochastic (Philox)" if rounding else "nearest",
                    "variant W (worker moments, Algorithms 2-3)" if variant_w else "variant S (server moments)"))
+    # the step as the GPU sees it: HIP events on the stream, from before its first kernel to after its last
+    gpu_ms = None if use_graph else scale_avg + main_avg
     out = dict(wl=wl, workload=workload, ms_per_step=ms_per_step, value=P / (ms_per_step * 1e-3), roofline=roofline,
+               gpu_ms=gpu_ms, step_bytes_per_param=(roofline.get("whole_step") or {}).get("bytes_per_param"),
                full_pass=full_pass, status=status, filtered=filtered, resident=sum(working_set),
                arena_bytes=B.arena_bytes, worker_elements=N * P / (ms_per_step * 1e-3))
     q.close()
@@ -512,6 +565,9 @@ def main():
     ap.add_argument("--ceilings", action="store_true",
                     help="also time plain torch streams over 6 GiB (an in-place update: half reads, half "
                          "writes; a device copy) and add them to the JSON line as memory_system")
+    ap.add_argument("--utilities", action="store_true",
+                    help="also time the kernels around the step alone (weight quantize / dequantize, the norm "
+                         "diagnostic) on the workload's vector and add them to the JSON line as utilities")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 4 GiB device copy (a kernel of known traffic, to scale "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -559,12 +615,12 @@ def main():
     }
     plain = args.variant == "s" and args.rounding == 0 and args.path == "fused" and not args.graph
     if plain and not args.no_other_configs and args.shrink == 1 and args.k_g is None and args.k_x is None:
-        # the other workloads, briefly, in the same launch configuration (separate allocations: they are small)
+        # the other workloads, briefly, in the same launch configuration and placement
         others = {}
         for c in (1, 2, 3, 4):
             if c == args.config:
                 continue
-            o = run_fused(args, c, dev, 5, 3, "separate", headline=False)
+            o = run_fused(args, c, dev, 20, 5, args.placement, headline=False)
             gc.collect()
             torch.cuda.empty_cache()
             rf = o["roofline"]
@@ -573,11 +629,18 @@ def main():
                 "main_pass_ms": rf["avg_launch_ms"], "main_pass_GBs": rf["achieved"],
                 "scale_pass": rf["scale_pass"]["mode"], "scale_pass_ms": rf["scale_pass"]["avg_launch_ms"],
                 "whole_step_GBs": rf["whole_step"]["GBs"], "whole_step_frac": rf["whole_step"]["frac"],
+                # the same bytes over the step's time on the GPU (HIP events around its launches; the wall time
+                # above also holds the host's launch and synchronisation cost, which dominates tiny steps)
+                "gpu_ms_per_step": round(o["gpu_ms"], 4),
+                "whole_step_frac_gpu_time": round(o["step_bytes_per_param"] * o["wl"].num_params / (o["gpu_ms"] * 1e-3) / 1e9
+                                                  / HBM_PEAK_GBS, 4),
                 "ms_per_step_full_scale_pass": o["full_pass"]["ms_per_step"] if o["full_pass"] else None,
                 "status_word": o["status"]}
         out["config"]["other_workloads"] = others
     if not args.no_cpu_baseline and plain and wl.k_g >= 0 and wl.k_x >= 0:
         out["cpu_baseline"] = cpu_baseline(wl, dev)
+    if args.utilities:
+        out["utilities"] = bench_utilities(wl, dev)
     if memory_system:
         out["memory_system"] = memory_system
     print(json.dumps(out), flush=True)

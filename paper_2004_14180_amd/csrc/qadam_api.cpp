@@ -31,7 +31,7 @@ struct qadam_ctx {
     uint32_t* d_thr;            // [num_workers][num_segments]
     int32_t*  d_sample_tiles;   // indices of the sampled tiles
     int32_t   num_sample_tiles;
-    bool      all_small;        // every layer is a small layer (handled by one workgroup, no scale pass)
+    bool      need_amax, need_reduce;   // which launches of the scale pass this layer list needs at all
     int       trust_errs;                       // qadam_trust_error_buffers: 0 off, 1 when it pays, 2 always, 3 verify
     bool      bound_valid[QADAM_MAX_WORKERS];   // d_err_bound row i describes what bound_err[i] now holds
     const float* bound_err[QADAM_MAX_WORKERS];  // the error buffer that row was recorded for
@@ -116,7 +116,7 @@ Launch make_launch(const qadam_ctx* h, void* stream)
     L.sample_tiles = h->d_sample_tiles; L.num_sample_tiles = h->num_sample_tiles;
     L.num_tiles = h->num_tiles; L.num_segments = h->num_segments;
     L.num_params = h->num_params; L.status = h->d_status; L.stream = static_cast<hipStream_t>(stream);
-    L.all_small = h->all_small;
+    L.need_amax = h->need_amax; L.need_reduce = h->need_reduce;
     return L;
 }
 
@@ -272,13 +272,15 @@ int qadam_init(qadam_handle_t* out, const qadam_config_t* cfg, const int64_t* se
     std::vector<int32_t> sample_tiles;
     std::vector<int32_t> seg_tile_begin(num_segments + 1, 0);
     int64_t word_off = 0;
-    bool all_small = true;
+    bool need_amax = false, need_reduce = false;
     for (int l = 0; l < num_segments; ++l) {
         seg_tile_begin[l] = (int32_t)tiles.size();
         const int64_t a = seg_offsets[l], n = seg_offsets[l + 1] - a;
         const int64_t seg_words = segment_code_words(h->code_bits, n);
         const int64_t used_words = (n + 31) / 32 * h->code_bits;
-        if (n == 0) all_small = false;          // an empty layer's scale (0) is written by the scale kernel
+        const int64_t layer_tiles = (n + h->tile_elems - 1) / h->tile_elems;
+        if (n == 0 || layer_tiles > kMediumLayerTiles) need_reduce = true;   // an empty layer's scale (0) comes from there too
+        if (n > kSmallLayerElems) need_amax = true;
         for (int64_t o = 0; o < n; o += h->tile_elems) {
             Tile t;
             t.start = a + o;
@@ -288,12 +290,12 @@ int qadam_init(qadam_handle_t* out, const qadam_config_t* cfg, const int64_t* se
             t.flags = (a % 4 != 0) ? kTileUnaligned : 0;
             if (o + h->tile_elems >= n) t.flags |= (int32_t)(seg_words - used_words) << 8;
             t.layer_len = 0;
+            if (layer_tiles <= kMediumLayerTiles) t.flags |= kTileMedium;
             if (n <= kSmallLayerElems) {
                 // one workgroup (that of the first tile) handles the whole layer; never a sampled tile
                 t.flags |= o == 0 ? kTileSmallHead : kTileSmallBody;
                 if (o == 0) t.layer_len = (int32_t)n;
             } else {
-                all_small = false;
                 if ((o / h->tile_elems) % kSampleStride == 0) {
                     t.flags |= kTileSampled;
                     sample_tiles.push_back((int32_t)tiles.size());
@@ -308,7 +310,8 @@ int qadam_init(qadam_handle_t* out, const qadam_config_t* cfg, const int64_t* se
     seg_tile_begin[num_segments] = (int32_t)tiles.size();
     h->num_tiles = (int32_t)tiles.size();
     h->num_sample_tiles = (int32_t)sample_tiles.size();
-    h->all_small = all_small;
+    h->need_amax = need_amax;
+    h->need_reduce = need_reduce;
 
     hipError_t e = hipGetDevice(&h->device);
     // set-up of the allocation-free entry point for this device (address of its static array), so that
@@ -406,7 +409,7 @@ int qadam_worker_quantize(qadam_handle_t h, int32_t worker, int64_t step, const 
     BoundRecord record(h, worker, 1, W);
     if (filtered) QADAM_HIP(launch_amax_filtered(L, S, W, worker, 1));
     else QADAM_HIP(launch_amax(L, S, W, worker, 1));
-    QADAM_HIP(launch_reduce_scales(L, S, W, worker, 1, true));
+    QADAM_HIP(launch_reduce_scales(L, S, W, worker, 1));
     QADAM_HIP(launch_worker_quantize(L, S, W, worker));
     record.complete = !capturing;       // nothing has run yet when the call was only recorded
     return QADAM_OK;
@@ -536,7 +539,7 @@ int qadam_step_fused(qadam_handle_t h, int64_t step, float lr, float beta2, cons
         BoundRecord record(h, 0, h->num_workers, W);
         if (filtered) QADAM_HIP(launch_amax_filtered(L, S, W, 0, h->num_workers));
         else QADAM_HIP(launch_amax(L, S, W, 0, h->num_workers));
-        QADAM_HIP(launch_reduce_scales(L, S, W, 0, h->num_workers, true));
+        QADAM_HIP(launch_reduce_scales(L, S, W, 0, h->num_workers));
         if (h->profile && !capturing) QADAM_HIP(hipEventRecord(h->ev[1], L.stream));
         QADAM_HIP(launch_fused(L, S, W, sp));
         record.complete = !capturing;
@@ -574,7 +577,7 @@ int qadam_worker_step_w(qadam_handle_t h, int32_t worker, int64_t step, float lr
     // pass 1: local moments, p = alpha m / sqrt(v + eps) + e parked in the error buffer, tile maxima
     BoundRecord record(h, worker, 1, W);
     QADAM_HIP(launch_worker_moments_w(L, S, W, worker, 1));
-    QADAM_HIP(launch_reduce_scales(L, S, W, worker, 1, false));
+    QADAM_HIP(launch_reduce_scales(L, S, W, worker, 1));
     // pass 2: quantize the parked p
     W.grad[worker] = nullptr;
     QADAM_HIP(launch_worker_quantize(L, S, W, worker));
@@ -612,7 +615,7 @@ int qadam_step_fused_w(qadam_handle_t h, int64_t step, float lr, float beta2, co
     // pass 1 (all workers): local moments, p parked in the error buffers, tile maxima; then scales
     BoundRecord record(h, 0, h->num_workers, W);
     QADAM_HIP(launch_worker_moments_w(L, S, W, 0, h->num_workers));
-    if (!idg) QADAM_HIP(launch_reduce_scales(L, S, W, 0, h->num_workers, false));
+    if (!idg) QADAM_HIP(launch_reduce_scales(L, S, W, 0, h->num_workers));
     if (h->profile && !capturing) QADAM_HIP(hipEventRecord(h->ev[1], L.stream));
     // pass 2: quantize every worker's parked p, subtract the mean message, Q_x
     if (idg) QADAM_HIP(launch_plain_messages(L, S, W, sp, true));

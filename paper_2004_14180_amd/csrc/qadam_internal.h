@@ -35,6 +35,11 @@ constexpr int kTileSampled = 2;
 constexpr int kTileSmallHead = 4;
 constexpr int kTileSmallBody = 8;
 constexpr int kSmallLayerElems = 4 * 4096;
+// A layer of at most kMediumLayerTiles tiles (small layers included) needs no launch of the kernel that
+// folds tile maxima into scales: every workgroup that quantizes one of its tiles folds the layer's few
+// tile maxima itself (they sit in L2), and the workgroup of the layer's first tile writes the scale out.
+constexpr int kTileMedium = 16;
+constexpr int kMediumLayerTiles = 640;
 constexpr int kSampleStride = 64;   // every 64th tile of a layer (from its first) is a sampled tile
 constexpr int kBlockThreads = 256;
 constexpr int kDefaultTileElems = 4096;   // elements per tile (16 per lane of a 256-thread workgroup)
@@ -87,7 +92,8 @@ struct Launch {
     const int32_t* sample_tiles;    // device: indices of the sampled tiles
     int32_t     num_sample_tiles;
     uint32_t*   status;     // device status word
-    bool        all_small;  // every layer is a small layer: the server-moments path needs no scale pass
+    bool        need_amax;   // server-moments path: some layer is neither small nor empty (else no tile-maxima launch)
+    bool        need_reduce; // some layer has more than kMediumLayerTiles tiles, or is empty (else no scale-folding launch)
     hipStream_t stream;
 };
 
@@ -95,10 +101,7 @@ struct Launch {
 // scales in two stages without atomics: per-tile maxima, then one workgroup per (worker, layer)
 // reduces its tiles and also writes the reciprocal used by the fast quotient
 hipError_t launch_amax(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker, int num);
-// skip_small: the small layers' scales come from the quantizing kernel (server-moments path); the
-// worker-moments path passes false (its first pass has produced every tile maximum)
-hipError_t launch_reduce_scales(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker, int num,
-                                bool skip_small);
+hipError_t launch_reduce_scales(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker, int num);
 hipError_t launch_amax_filtered(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker, int num);
 hipError_t launch_check_error_bounds(const Launch& L, const WorkerPtrs& W, int first_worker, int num);
 hipError_t launch_worker_quantize(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int worker);

@@ -422,8 +422,10 @@ struct FusedArgs {
     int num_tiles;
     uint32_t* status;
     float* inv_scales;            // [N][L]
-    float* err_bound;             // [N][L], written for small layers (the scale kernels write the others)
+    float* err_bound;             // [N][L], written for small and medium layers (the scale kernel writes the others)
     float bound_factor;
+    const uint32_t* tile_max;     // [N][num_tiles]
+    const int32_t* seg_tile_begin;
     int num_segments;
     StepScalars S;
     ServerPtrs sp;
@@ -443,8 +445,10 @@ struct WorkerArgs {        // one worker
     uint32_t* codes;
     float* scales;
     float* inv_scales;         // this worker's row
-    float* err_bound;          // this worker's row, written for small layers
+    float* err_bound;          // this worker's row, written for small and medium layers
     float bound_factor;
+    const uint32_t* tile_max;  // this worker's row
+    const int32_t* seg_tile_begin;
     int worker;
     int64_t seg_len;           // tiles == null only: length of the single segment
 };
@@ -480,8 +484,7 @@ struct ScaleArgs {
     uint32_t* thr;          // [N][L]: thresholds of the filtered pass (written by k_reduce_lower_bounds)
     float bound_factor;     // |e'| <= bound_factor * s for this quantizer and rounding mode
     int sample_stride;      // every sample_stride-th tile of a layer is a sampled tile
-    const Tile* tiles;      // with skip_small: to recognise the small layers
-    int skip_small;         // non-zero: small layers get their scales from the quantizing kernel
+    const Tile* tiles;      // to recognise the layers whose scales the quantizing kernel folds itself (null: none)
 };
 
 // ------------------------------------------------------------------------------------------------
@@ -545,7 +548,7 @@ __device__ __forceinline__ uint32_t small_layer_wave_max(const float* __restrict
 // keeps them in LDS for the workgroup and writes scale, reciprocal and residual bound to global memory.
 __device__ __forceinline__ void small_layer_finish(SmallLayerShared& sh, int first, int count, int seg, int num_segments,
                                                    float* const* scales, float* inv_scales, float* err_bound,
-                                                   float bound_factor, bool per_worker_rows)
+                                                   float bound_factor, bool per_worker_rows, bool write_global = true)
 {
     __syncthreads();
     if ((int)threadIdx.x < count) {
@@ -558,13 +561,26 @@ __device__ __forceinline__ void small_layer_finish(SmallLayerShared& sh, int fir
         const float inv = ok ? 1.0f / s : 0.0f;
         sh.scale[i] = s;
         sh.inv[i] = inv;
-        // per_worker_rows: the table pointers address worker i's row; else row i of an [N][L] table
-        const size_t row = per_worker_rows ? 0 : (size_t)i * num_segments;
-        scales[per_worker_rows ? 0 : i][seg] = s;
-        inv_scales[row + seg] = inv;
-        err_bound[row + seg] = s * bound_factor + 0x1p-140f;
+        if (write_global) {
+            // per_worker_rows: the table pointers address worker i's row; else row i of an [N][L] table
+            const size_t row = per_worker_rows ? 0 : (size_t)i * num_segments;
+            scales[per_worker_rows ? 0 : i][seg] = s;
+            inv_scales[row + seg] = inv;
+            err_bound[row + seg] = s * bound_factor + 0x1p-140f;
+        }
     }
     __syncthreads();
+}
+
+// this wavefront's share of the max over the tile maxima [t0, t1) of one worker (medium layers)
+__device__ __forceinline__ uint32_t medium_layer_wave_max(const uint32_t* __restrict__ tile_max_row, int t0, int t1)
+{
+    uint32_t local = 0;
+    for (int t = t0 + (int)threadIdx.x; t < t1; t += kBlockThreads) {
+        const uint32_t v = tile_max_row[t];
+        local = v > local ? v : local;
+    }
+    return wave_max_u32(local);
 }
 
 // grid: (layers, workers).  One workgroup folds the tile maxima of its (worker, layer).
@@ -574,7 +590,7 @@ __global__ void __launch_bounds__(kBlockThreads) k_reduce_scales(ScaleArgs A)
     // no table: a single segment that owns every tile
     const int t0 = A.seg_tile_begin ? A.seg_tile_begin[l] : 0;
     const int t1 = A.seg_tile_begin ? A.seg_tile_begin[l + 1] : A.num_tiles;
-    if (A.skip_small && t1 > t0 && (A.tiles[t0].flags & kTileSmallHead)) return;
+    if (A.tiles && t1 > t0 && (A.tiles[t0].flags & kTileMedium)) return;
     const uint32_t* part = A.tile_max + (size_t)w * A.num_tiles;
     uint32_t local = 0;
     for (int t = t0 + threadIdx.x; t < t1; t += kBlockThreads) {
@@ -604,7 +620,7 @@ __global__ void __launch_bounds__(kBlockThreads) k_reduce_lower_bounds(ScaleArgs
 {
     const int l = blockIdx.x, w = A.first_worker + blockIdx.y;
     const int t0 = A.seg_tile_begin[l], t1 = A.seg_tile_begin[l + 1];
-    if (A.skip_small && t1 > t0 && (A.tiles[t0].flags & kTileSmallHead)) return;
+    if (t1 > t0 && (A.tiles[t0].flags & kTileSmallHead)) return;
     const uint32_t* part = A.tile_max + (size_t)w * A.num_tiles;
     uint32_t local = 0;
     for (int t = t0 + (int)threadIdx.x * A.sample_stride; t < t1; t += kBlockThreads * A.sample_stride) {
@@ -755,6 +771,24 @@ __global__ void __launch_bounds__(kBlockThreads) k_amax_filtered(AmaxArgs A)
     if (threadIdx.x == 0) A.tile_max[(size_t)w * A.num_tiles + ti] = bm;
 }
 
+// max |e| over a tile
+template <int V>
+__device__ __forceinline__ uint32_t emax_tile(const float* __restrict__ e, const Tile& t)
+{
+    uint32_t local = 0;
+    for (int off = threadIdx.x * V; off < t.len; off += kBlockThreads * V) {
+        const int nvalid = min(t.len - off, V);
+        float ev[V];
+        load_v<V>(e + t.start + off, nvalid, ev);
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            const uint32_t ab = f2u(ev[j]) & 0x7fffffffu;
+            local = ab > local ? ab : local;
+        }
+    }
+    return local;
+}
+
 // Verification of the contract behind the filtered pass (bring-up aid): every |e_j| must be within
 // the bound the previous step recorded for its layer.  grid: (tiles, workers); reads e only.
 __global__ void __launch_bounds__(kBlockThreads) k_check_error_bounds(AmaxArgs A)
@@ -763,11 +797,7 @@ __global__ void __launch_bounds__(kBlockThreads) k_check_error_bounds(AmaxArgs A
     const Tile t = A.tiles[ti];
     const int w = A.first_worker + blockIdx.y;
     const float* e = A.err[w];
-    uint32_t local = 0;
-    for (int off = threadIdx.x; off < t.len; off += kBlockThreads) {
-        const uint32_t ab = f2u(e[t.start + off]) & 0x7fffffffu;
-        local = ab > local ? ab : local;
-    }
+    const uint32_t local = (t.flags & kTileUnaligned) ? emax_tile<1>(e, t) : emax_tile<4>(e, t);
     const uint32_t bm = block_max(local);
     if (threadIdx.x == 0) {
         const float bound = A.err_bound[(size_t)w * A.num_segments + t.seg];
@@ -887,6 +917,18 @@ __global__ void __launch_bounds__(kBlockThreads) k_worker_quantize(WorkerArgs A)
             return;
         }
     }
+    if (t.flags & kTileMedium) {
+        // the layer has few tiles: fold their maxima here instead of in a launch of its own
+        __shared__ SmallLayerShared sh;
+        const int t0 = A.seg_tile_begin[t.seg], t1 = A.seg_tile_begin[t.seg + 1];
+        const uint32_t wm = medium_layer_wave_max(A.tile_max, t0, t1);
+        if ((threadIdx.x & 63) == 0) sh.part[0][threadIdx.x >> 6] = wm;
+        float* scales_row[1] = {A.scales};
+        small_layer_finish(sh, 0, 1, t.seg, 1, scales_row, A.inv_scales, A.err_bound, A.bound_factor, true, ti == t0);
+        if (t.flags & kTileUnaligned) worker_tile<1, ROUNDING, PARKED, true>(A, t, &sh);
+        else worker_tile<4, ROUNDING, PARKED, true>(A, t, &sh);
+        return;
+    }
     if (t.flags & kTileUnaligned) worker_tile<1, ROUNDING, PARKED>(A, t);
     else worker_tile<4, ROUNDING, PARKED>(A, t);
 }
@@ -974,22 +1016,35 @@ struct WeightArgs {
     int64_t n;
 };
 
+// One workgroup per 4096 consecutive elements; a lane owns four quads, quad k being elements
+// 4 * (lane + 256 k) .. + 3, and issues the loads of all four before any arithmetic.
 template <int ROUNDING>
 __global__ void __launch_bounds__(kBlockThreads) k_weight_quantize(WeightArgs A)
 {
     const StepScalars& S = A.S;
-    const int64_t quads = (A.n + 3) / 4;
-    for (int64_t qd = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; qd < quads;
-         qd += (int64_t)gridDim.x * blockDim.x) {
-        const int64_t gi = qd * 4;
-        const int nvalid = (int)min((int64_t)4, A.n - gi);
-        float xv[4], wi[4] = {0.f, 0.f, 0.f, 0.f}, wo[4];
+    const int64_t base = (int64_t)blockIdx.x * (kBlockThreads * 16);
+    float xv[4][4], wi[4][4];
+    int nvalid[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int64_t gi = base + 4 * ((int64_t)threadIdx.x + kBlockThreads * k);
+        nvalid[k] = (int)max((int64_t)0, min((int64_t)4, A.n - gi));
+#pragma unroll
+        for (int t = 0; t < 4; ++t) wi[k][t] = 0.0f;
+        if (nvalid[k] > 0) {
+            load_v<4>(A.x + gi, nvalid[k], xv[k]);
+            if (S.weight_ef) load_v<4>(A.werr + gi, nvalid[k], wi[k]);
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        if (nvalid[k] == 0) continue;
+        const int64_t gi = base + 4 * ((int64_t)threadIdx.x + kBlockThreads * k);
+        float wo[4];
         int j[4];
-        load_v<4>(A.x + gi, nvalid, xv);
-        if (S.weight_ef) load_v<4>(A.werr + gi, nvalid, wi);
-        weight_lane<4, ROUNDING>(S, xv, wi, gi, wo, j);
-        if (A.werr) store_v<4>(A.werr + gi, nvalid, wo);
-        store_wcodes<4>(A.wcodes, S.wcode_bytes, gi, nvalid, j);
+        weight_lane<4, ROUNDING>(S, xv[k], wi[k], gi, wo, j);
+        if (A.werr) store_v<4>(A.werr + gi, nvalid[k], wo);
+        store_wcodes<4>(A.wcodes, S.wcode_bytes, gi, nvalid[k], j);
     }
 }
 
@@ -1001,16 +1056,83 @@ struct DequantArgs {
     float inv_two_kx1;
 };
 
-template <bool HALF>
+// A lane owns four pieces of E consecutive codes (E = 4 for fp32 output, 8 for binary16, so that an output
+// store is always 128 bits), piece k being elements E * (lane + 256 k) .. of the workgroup's 1024 E codes:
+// every store of a wavefront is one contiguous 1 KiB run and the four code loads are issued together.
+typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u2 __attribute__((ext_vector_type(2)));
+
+template <bool HALF, int CODE_BYTES>
 __global__ void __launch_bounds__(kBlockThreads) k_weight_dequantize(DequantArgs A)
 {
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < A.n;
-         i += (int64_t)gridDim.x * blockDim.x) {
-        const int j = A.wcode_bytes == 1 ? (int)static_cast<const int8_t*>(A.wcodes)[i]
-                                         : (int)static_cast<const int16_t*>(A.wcodes)[i];
-        const float xh = (float)j * A.inv_two_kx1;
-        if constexpr (HALF) static_cast<__half*>(A.xhat)[i] = __float2half_rn(xh);
-        else static_cast<float*>(A.xhat)[i] = xh;
+    constexpr int E = HALF ? 8 : 4;
+    constexpr int WORDS = E * CODE_BYTES / 4;           // code words per piece: 1, 2 or 4
+    const int64_t base = (int64_t)blockIdx.x * (kBlockThreads * E * 4);
+    uint32_t w[4][WORDS];
+    bool full[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int64_t i = base + E * ((int64_t)threadIdx.x + kBlockThreads * k);
+        full[k] = i + E <= A.n;
+#pragma unroll
+        for (int t = 0; t < WORDS; ++t) w[k][t] = 0u;
+        const char* src = static_cast<const char*>(A.wcodes) + i * CODE_BYTES;
+        if (full[k]) {
+            if constexpr (WORDS == 1) {
+                w[k][0] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(src));
+            } else if constexpr (WORDS == 2) {
+                const u2 v = __builtin_nontemporal_load(reinterpret_cast<const u2*>(src));
+                w[k][0] = v.x; w[k][1] = v.y;
+            } else {
+                const u4 v = __builtin_nontemporal_load(reinterpret_cast<const u4*>(src));
+                w[k][0] = v.x; w[k][1] = v.y; w[k][2] = v.z; w[k][3] = v.w;
+            }
+        } else {
+            // ragged end of the vector: code by code
+#pragma unroll
+            for (int t = 0; t < E; ++t) {
+                if (i + t < A.n) {
+                    const uint32_t c = CODE_BYTES == 1 ? (uint32_t)(uint8_t)src[t]
+                                                       : (uint32_t)reinterpret_cast<const uint16_t*>(src)[t];
+                    w[k][t * CODE_BYTES / 4] |= c << (8 * ((t * CODE_BYTES) & 3));
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int64_t i = base + E * ((int64_t)threadIdx.x + kBlockThreads * k);
+        float xh[E];
+#pragma unroll
+        for (int t = 0; t < E; ++t) {
+            const uint32_t c = w[k][t * CODE_BYTES / 4] >> (8 * ((t * CODE_BYTES) & 3));
+            const int j = CODE_BYTES == 1 ? (int)(int8_t)c : (int)(int16_t)c;
+            xh[t] = (float)j * A.inv_two_kx1;
+        }
+        if constexpr (HALF) {
+            __half* out = static_cast<__half*>(A.xhat) + i;
+            if (full[k]) {
+                u4 v;
+                v.x = (uint32_t)__half_as_ushort(__float2half_rn(xh[0])) | ((uint32_t)__half_as_ushort(__float2half_rn(xh[1])) << 16);
+                v.y = (uint32_t)__half_as_ushort(__float2half_rn(xh[2])) | ((uint32_t)__half_as_ushort(__float2half_rn(xh[3])) << 16);
+                v.z = (uint32_t)__half_as_ushort(__float2half_rn(xh[4])) | ((uint32_t)__half_as_ushort(__float2half_rn(xh[5])) << 16);
+                v.w = (uint32_t)__half_as_ushort(__float2half_rn(xh[6])) | ((uint32_t)__half_as_ushort(__float2half_rn(xh[7])) << 16);
+                __builtin_nontemporal_store(v, reinterpret_cast<u4*>(out));
+            } else {
+#pragma unroll
+                for (int t = 0; t < E; ++t) if (i + t < A.n) out[t] = __float2half_rn(xh[t]);
+            }
+        } else {
+            float* out = static_cast<float*>(A.xhat) + i;
+            if (full[k]) {
+                f4 v;
+                v.x = xh[0]; v.y = xh[1]; v.z = xh[2]; v.w = xh[3];
+                __builtin_nontemporal_store(v, reinterpret_cast<f4*>(out));
+            } else {
+#pragma unroll
+                for (int t = 0; t < E; ++t) if (i + t < A.n) out[t] = xh[t];
+            }
+        }
     }
 }
 
@@ -1141,6 +1263,21 @@ __global__ void __launch_bounds__(kBlockThreads) k_fused(FusedArgs A)
             fused_small_layer<ROUNDING, U>(A, t);
             return;
         }
+    }
+    if (t.flags & kTileMedium) {
+        // the layer has few tiles: fold their maxima here instead of in a launch of its own
+        __shared__ SmallLayerShared sh;
+        const int N = A.S.num_workers;
+        const int t0 = A.seg_tile_begin[t.seg], t1 = A.seg_tile_begin[t.seg + 1];
+        for (int i = 0; i < N; ++i) {
+            const uint32_t wm = medium_layer_wave_max(A.tile_max + (size_t)i * A.num_tiles, t0, t1);
+            if ((threadIdx.x & 63) == 0) sh.part[i][threadIdx.x >> 6] = wm;
+        }
+        small_layer_finish(sh, 0, N, t.seg, A.num_segments, A.scales, A.inv_scales, A.err_bound, A.bound_factor, false,
+                           ti == t0);
+        if (t.flags & kTileUnaligned) fused_tile<1, ROUNDING, 1, W, true>(A, t, &sh);
+        else fused_tile<4, ROUNDING, U, W, true>(A, t, &sh);
+        return;
     }
     if (t.flags & kTileUnaligned) fused_tile<1, ROUNDING, 1, W>(A, t);
     else fused_tile<4, ROUNDING, U, W>(A, t);
@@ -1346,15 +1483,6 @@ __global__ void __launch_bounds__(kBlockThreads) k_sumsq_layers(SumsqArgs A)
     if (threadIdx.x == 0) A.out[l] = s;
 }
 
-int grid_for(int64_t work_items, int per_block)
-{
-    int64_t blocks = (work_items + per_block - 1) / per_block;
-    const int64_t cap = 256 * 64;      // 256 CUs, grid-stride beyond that
-    if (blocks > cap) blocks = cap;
-    if (blocks < 1) blocks = 1;
-    return (int)blocks;
-}
-
 }  // namespace
 
 // ================================================================================================
@@ -1369,10 +1497,9 @@ static float residual_bound_factor(const StepScalars& S)
     return (S.rounding == 0 ? half_gap : 2.0f * half_gap) * (1.0f + 0x1p-20f);
 }
 
-static void fill_scale_args(ScaleArgs& A, const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker,
-                            bool skip_small)
+static void fill_scale_args(ScaleArgs& A, const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker)
 {
-    A.tiles = L.tiles; A.skip_small = skip_small ? 1 : 0;
+    A.tiles = L.tiles;
     for (int i = 0; i < QADAM_MAX_WORKERS; ++i) A.scales[i] = W.scales[i];
     A.inv_scales = L.inv_scales; A.tile_max = L.tile_max; A.seg_tile_begin = L.seg_tile_begin;
     A.first_worker = first_worker; A.num_segments = L.num_segments; A.num_tiles = L.num_tiles;
@@ -1381,13 +1508,12 @@ static void fill_scale_args(ScaleArgs& A, const Launch& L, const StepScalars& S,
     A.sample_stride = kSampleStride;
 }
 
-hipError_t launch_reduce_scales(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker, int num,
-                                bool skip_small)
+hipError_t launch_reduce_scales(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker, int num)
 {
     if (L.num_segments == 0 || num == 0) return hipSuccess;
-    if (skip_small && L.all_small) return hipSuccess;      // every scale comes from the quantizing kernel
+    if (!L.need_reduce) return hipSuccess;      // every scale is folded by the quantizing kernel
     ScaleArgs A;
-    fill_scale_args(A, L, S, W, first_worker, skip_small);
+    fill_scale_args(A, L, S, W, first_worker);
     hipLaunchKernelGGL(k_reduce_scales, dim3(L.num_segments, num), dim3(kBlockThreads), 0, L.stream, A);
     return hipGetLastError();
 }
@@ -1417,7 +1543,7 @@ hipError_t launch_check_error_bounds(const Launch& L, const WorkerPtrs& W, int f
 hipError_t launch_amax(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker, int num)
 {
     (void)S;
-    if (L.num_tiles == 0 || num == 0 || L.all_small) return hipSuccess;
+    if (L.num_tiles == 0 || num == 0 || !L.need_amax) return hipSuccess;
     AmaxArgs A;
     fill_amax_args(A, L, W, first_worker);
     hipLaunchKernelGGL(k_amax, dim3(L.num_tiles, num), dim3(kBlockThreads), 0, L.stream, A);
@@ -1429,13 +1555,13 @@ hipError_t launch_amax(const Launch& L, const StepScalars& S, const WorkerPtrs& 
 // where |g| reaches the threshold.  launch_reduce_scales follows as usual.
 hipError_t launch_amax_filtered(const Launch& L, const StepScalars& S, const WorkerPtrs& W, int first_worker, int num)
 {
-    if (L.num_tiles == 0 || num == 0 || L.all_small) return hipSuccess;
+    if (L.num_tiles == 0 || num == 0 || !L.need_amax) return hipSuccess;
     AmaxArgs A;
     fill_amax_args(A, L, W, first_worker);
     A.tile_list = L.sample_tiles;
     hipLaunchKernelGGL(k_amax, dim3(L.num_sample_tiles, num), dim3(kBlockThreads), 0, L.stream, A);
     ScaleArgs R;
-    fill_scale_args(R, L, S, W, first_worker, true);
+    fill_scale_args(R, L, S, W, first_worker);
     hipLaunchKernelGGL(k_reduce_lower_bounds, dim3(L.num_segments, num), dim3(kBlockThreads), 0, L.stream, R);
     A.tile_list = nullptr;
     hipLaunchKernelGGL(k_amax_filtered, dim3(L.num_tiles, num), dim3(kBlockThreads), 0, L.stream, A);
@@ -1452,6 +1578,8 @@ hipError_t launch_worker_quantize(const Launch& L, const StepScalars& S, const W
     A.inv_scales = L.inv_scales + (size_t)worker * L.num_segments;
     A.err_bound = L.err_bound + (size_t)worker * L.num_segments;
     A.bound_factor = residual_bound_factor(S);
+    A.tile_max = L.tile_max + (size_t)worker * L.num_tiles;
+    A.seg_tile_begin = L.seg_tile_begin;
     A.worker = worker;
     A.seg_len = 0;
     const bool parked = (A.grad == nullptr);
@@ -1512,7 +1640,7 @@ hipError_t launch_weight_quantize(const Launch& L, const StepScalars& S, const f
     if (L.num_params == 0) return hipSuccess;
     WeightArgs A;
     A.S = S; A.x = x; A.werr = werr; A.wcodes = wcodes; A.n = L.num_params;
-    const dim3 grid(grid_for((L.num_params + 3) / 4, kBlockThreads)), block(kBlockThreads);
+    const dim3 grid((unsigned)((L.num_params + kBlockThreads * 16 - 1) / (kBlockThreads * 16))), block(kBlockThreads);
     if (S.rounding == 0) hipLaunchKernelGGL(k_weight_quantize<0>, grid, block, 0, L.stream, A);
     else hipLaunchKernelGGL(k_weight_quantize<1>, grid, block, 0, L.stream, A);
     return hipGetLastError();
@@ -1526,9 +1654,15 @@ hipError_t launch_weight_dequantize(const Launch& L, const StepScalars& S, const
     union { uint32_t u; float f; } cv;
     cv.u = (uint32_t)(127 - S.k_x - 1) << 23;
     A.inv_two_kx1 = cv.f;
-    const dim3 grid(grid_for(L.num_params, kBlockThreads)), block(kBlockThreads);
-    if (half) hipLaunchKernelGGL(k_weight_dequantize<true>, grid, block, 0, L.stream, A);
-    else hipLaunchKernelGGL(k_weight_dequantize<false>, grid, block, 0, L.stream, A);
+    const int64_t per_block = (int64_t)kBlockThreads * 4 * (half ? 8 : 4);
+    const dim3 grid((unsigned)((L.num_params + per_block - 1) / per_block)), block(kBlockThreads);
+    if (S.wcode_bytes == 1) {
+        if (half) hipLaunchKernelGGL((k_weight_dequantize<true, 1>), grid, block, 0, L.stream, A);
+        else hipLaunchKernelGGL((k_weight_dequantize<false, 1>), grid, block, 0, L.stream, A);
+    } else {
+        if (half) hipLaunchKernelGGL((k_weight_dequantize<true, 2>), grid, block, 0, L.stream, A);
+        else hipLaunchKernelGGL((k_weight_dequantize<false, 2>), grid, block, 0, L.stream, A);
+    }
     return hipGetLastError();
 }
 
@@ -1540,6 +1674,7 @@ static hipError_t launch_fused_any(const Launch& L, const StepScalars& S, const 
     A.tiles = L.tiles; A.num_tiles = L.num_tiles;
     A.status = L.status; A.inv_scales = L.inv_scales; A.num_segments = L.num_segments; A.S = S; A.sp = sp;
     A.err_bound = L.err_bound; A.bound_factor = residual_bound_factor(S);
+    A.tile_max = L.tile_max; A.seg_tile_begin = L.seg_tile_begin;
     for (int i = 0; i < QADAM_MAX_WORKERS; ++i) {
         A.grad[i] = W.grad[i]; A.err[i] = W.err[i]; A.codes[i] = W.codes[i]; A.scales[i] = W.scales[i];
     }
@@ -1575,6 +1710,7 @@ hipError_t launch_plain_messages(const Launch& L, const StepScalars& S, const Wo
     A.tiles = L.tiles; A.num_tiles = L.num_tiles;
     A.status = L.status; A.inv_scales = L.inv_scales; A.num_segments = L.num_segments; A.S = S; A.sp = sp;
     A.err_bound = L.err_bound; A.bound_factor = 0.0f;
+    A.tile_max = L.tile_max; A.seg_tile_begin = L.seg_tile_begin;
     for (int i = 0; i < QADAM_MAX_WORKERS; ++i) {
         A.grad[i] = W.grad[i]; A.err[i] = W.err[i]; A.codes[i] = nullptr; A.scales[i] = nullptr;
     }
@@ -1695,7 +1831,7 @@ hipError_t noalloc_quantize_segment(const StepScalars& S, int64_t n, const float
     R.err_bound = err_bound; R.thr = nullptr;
     R.bound_factor = residual_bound_factor(S);
     R.sample_stride = kSampleStride;
-    R.tiles = nullptr; R.skip_small = 0;
+    R.tiles = nullptr;
     hipLaunchKernelGGL(k_reduce_scales, dim3(1, 1), dim3(kBlockThreads), 0, stream, R);
     if (num_tiles > 0) {
         WorkerArgs W;
@@ -1704,6 +1840,7 @@ hipError_t noalloc_quantize_segment(const StepScalars& S, int64_t n, const float
         W.status = status; W.S = S;
         W.grad = grad; W.err = err; W.codes = codes; W.scales = scale_out; W.inv_scales = inv_scale;
         W.err_bound = err_bound; W.bound_factor = residual_bound_factor(S);
+        W.tile_max = tile_max; W.seg_tile_begin = nullptr;
         W.worker = 0;
         hipLaunchKernelGGL((k_worker_quantize<0, false>), dim3(num_tiles), dim3(kBlockThreads), 0, stream, W);
     }

@@ -368,7 +368,7 @@ def run_fused(args, config, dev, steps, warmup, placement, headline):
     from paper_2004_14180_amd import QAdam, QAdamConfig
     from paper_2004_14180_amd.workloads import make_workload
 
-    wl = make_workload(config, shrink=args.shrink if headline else 1)
+    wl = make_workload(config, shrink=args.shrink if headline else 1, misalign=bool(headline and args.misalign))
     if headline and args.k_g is not None:
         wl.k_g = args.k_g
     if headline and args.k_x is not None:
@@ -545,6 +545,10 @@ def main():
     ap.add_argument("--placement", choices=["arena", "separate"], default="arena",
                     help="arena: one allocation, buffers at the offsets of qadam_arena_layout; separate: one "
                          "allocation per buffer")
+    ap.add_argument("--misalign", action="store_true",
+                    help="put one 1001-element layer in front of the workload's layer list, so that every other "
+                         "layer starts off a 16-byte boundary (the kernels then shift data between lanes to keep "
+                         "their memory accesses aligned)")
     ap.add_argument("--graph", action="store_true",
                     help="capture the step in a HIP graph after the warm-up and time replays of it (pays on "
                          "launch-bound workloads such as config 1; kernels are then not timed one by one)")
@@ -614,7 +618,8 @@ def main():
         "roofline": r["roofline"],
     }
     plain = args.variant == "s" and args.rounding == 0 and args.path == "fused" and not args.graph
-    if plain and not args.no_other_configs and args.shrink == 1 and args.k_g is None and args.k_x is None:
+    if plain and not args.no_other_configs and args.shrink == 1 and args.k_g is None and args.k_x is None \
+            and not args.misalign:
         # the other workloads, briefly, in the same launch configuration and placement
         others = {}
         for c in (1, 2, 3, 4):

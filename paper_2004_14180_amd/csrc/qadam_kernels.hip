@@ -14,9 +14,14 @@
 //   * the per-layer scale is a max over |g+e|: lanes reduce with integer max on the bit pattern
 //     (non-negative floats order like integers; NaN/Inf sort above every finite value and so
 //     surface in the scale), wavefront reduction by cross-lane shuffles, LDS across the four
-//     wavefronts, one plain store of the tile's maximum; a second small kernel reduces the tiles of
-//     each (worker, layer).  No atomics: thousands of workgroups hitting one freshly zeroed word
-//     at the start of every layer cost more than the whole pass;
+//     wavefronts, one plain store of the tile's maximum; the tile maxima of a layer are folded by a
+//     second small kernel (layers of more than 640 tiles) or by the quantizing workgroups themselves
+//     (smaller layers: the few maxima sit in L2, and the launch is saved).  No atomics: thousands of
+//     workgroups hitting one freshly zeroed word at the start of every layer cost more than the whole pass;
+//   * a layer of at most 16384 elements is done by ONE workgroup, scale included: g and e are read
+//     once from memory (the quantizing phase finds them in cache), no scale pass is needed for it;
+//   * a segment that starts off the 16-byte grid keeps the same lane-to-element mapping (the codes are
+//     anchored at the segment start) and moves its data with dword-aligned 128-bit accesses;
 //   * when the error buffers are what the previous step wrote, |e| <= s/4 (half the widest gap of
 //     the grid), so an element whose |g| lies that far below a known lower bound of the scale
 //     cannot be the maximum: the filtered scale pass takes the exact maxima of every 64th tile as
@@ -42,6 +47,8 @@ namespace {
 
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef short s4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ uint32_t f2u(float f) { return __float_as_uint(f); }
 __device__ __forceinline__ float u2f(uint32_t u) { return __uint_as_float(u); }
@@ -200,13 +207,12 @@ __device__ __forceinline__ float qg_decode_planes(const uint32_t (&w)[4], uint32
 }
 
 // ------------------------------------------------------------------------------------------------
-// Bit-plane packing.  V == 4: a lane holds the codes of elements 4*lane..4*lane+3 of a 256-element
+// Bit-plane packing.  A lane holds the codes of elements 4*lane..4*lane+3 of a 256-element
 // wave chunk as four nibbles of `codes`; the 8 lanes 8G..8G+7 form 32-element group G.  For plane k
 // every lane gathers its 4 plane bits (a multiply moves bits 0,4,8,12 to bits 9..12), shifts them
 // to position 4*(lane%8) and the group ORs them with three DPP steps (swap within pairs, swap
 // pairs within quads, mirror the two quads of a half row).  Lane 8G+k keeps word k.  Must be
 // called with all 64 lanes active.
-// V == 1: lane = element; a wave ballot of plane k is the two words of the chunk's two groups.
 // ------------------------------------------------------------------------------------------------
 __device__ __forceinline__ uint32_t dpp_or8(uint32_t w)
 {
@@ -235,18 +241,6 @@ __device__ __forceinline__ uint32_t pack_planes(uint32_t codes, int code_bits, i
         }
         word_slot = (lane >> 3) * code_bits + sub;     // word within the wave chunk's 8 groups
         writes = sub < code_bits;
-    } else {
-        const int grp = lane / code_bits, k_mine = lane - grp * code_bits;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            if (k < code_bits) {
-                const unsigned long long mask = __ballot((codes >> k) & 1u);
-                const uint32_t w = grp == 0 ? (uint32_t)mask : (uint32_t)(mask >> 32);
-                sel = k_mine == k ? w : sel;
-            }
-        }
-        word_slot = lane;                              // lanes 0 .. 2*code_bits-1 hold the chunk's words
-        writes = lane < 2 * code_bits;
     }
     return sel;
 }
@@ -257,10 +251,11 @@ template <int V, int MU_BITS>
 __device__ __forceinline__ uint32_t load_planes(const uint32_t* __restrict__ chunk_words, int lane, uint32_t (&w)[4])
 {
     constexpr int CODE_BITS = MU_BITS + 1;
-    const uint32_t* gw = chunk_words + (V == 4 ? (lane >> 3) : (lane >> 5)) * CODE_BITS;
+    static_assert(V == 4, "a lane owns four consecutive elements");
+    const uint32_t* gw = chunk_words + (lane >> 3) * CODE_BITS;
 #pragma unroll
     for (int k = 0; k < 4; ++k) w[k] = k < CODE_BITS ? gw[k] : 0u;
-    return V == 4 ? (uint32_t)(lane & 7) * 4u : (uint32_t)(lane & 31);
+    return (uint32_t)(lane & 7) * 4u;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -334,6 +329,128 @@ __device__ __forceinline__ void store_wcodes(void* __restrict__ base, int wcode_
 }
 
 // ------------------------------------------------------------------------------------------------
+// Tiles of a segment that does not start on a 16-byte boundary.  The packed codes are anchored at the
+// segment start (a lane's four elements are four consecutive bits of a plane word), so a lane's four
+// values lie r = (flat start mod 4) floats off the 16-byte grid of memory.  The lane still moves them
+// with ONE 128-bit access: the vector type below carries 4-byte alignment, for which the compiler emits
+// the same global_load/store_dwordx4 (the memory unit of this target accepts dword-aligned wide
+// accesses); a wavefront's access is still one contiguous 1 KiB run, it merely touches nine 128-byte
+// lines instead of eight.  The weight codes (four int8 or int16) are stored likewise through types of
+// element alignment.  What differs besides is the random stream of stochastic rounding, which is
+// indexed by the flat element number (below).
+// ------------------------------------------------------------------------------------------------
+typedef f4 f4_a4 __attribute__((aligned(4)));
+typedef uint32_t u32_a1 __attribute__((aligned(1)));
+typedef s4 s4_a2 __attribute__((aligned(2)));
+
+struct Shift {
+    int r;              // flat index of the tile's first element mod 4 (1..3 when used)
+};
+
+__device__ __forceinline__ Shift make_shift(const Tile& t)
+{
+    Shift sf;
+    sf.r = (int)(t.start & 3);
+    return sf;
+}
+
+__device__ __forceinline__ void load_shifted(const float* __restrict__ p, int nvalid, float (&out)[4])
+{
+    if (nvalid == 4) {
+        const f4 t = *reinterpret_cast<const f4_a4*>(p);
+        out[0] = t.x; out[1] = t.y; out[2] = t.z; out[3] = t.w;
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) out[j] = j < nvalid ? p[j] : 0.0f;
+    }
+}
+
+__device__ __forceinline__ void store_shifted(float* __restrict__ p, int nvalid, const float (&in)[4])
+{
+    if (nvalid == 4) {
+        f4 t;
+        t.x = in[0]; t.y = in[1]; t.z = in[2]; t.w = in[3];
+        __builtin_nontemporal_store(t, reinterpret_cast<f4_a4*>(p));
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) if (j < nvalid) p[j] = in[j];
+    }
+}
+
+// weight codes of the lane's four elements at element index gi (not a multiple of 4)
+__device__ __forceinline__ void store_wcodes_shifted(void* __restrict__ base, int wcode_bytes, int64_t gi, int nvalid,
+                                                     const int (&j)[4])
+{
+    if (wcode_bytes == 1) {
+        int8_t* p = static_cast<int8_t*>(base) + gi;
+        if (nvalid == 4) {
+            const uint32_t packed = ((uint32_t)j[0] & 0xFFu) | (((uint32_t)j[1] & 0xFFu) << 8) |
+                                    (((uint32_t)j[2] & 0xFFu) << 16) | ((uint32_t)j[3] << 24);
+            __builtin_nontemporal_store(packed, reinterpret_cast<u32_a1*>(p));
+            return;
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) if (t < nvalid) p[t] = (int8_t)j[t];
+    } else {
+        int16_t* p = static_cast<int16_t*>(base) + gi;
+        if (nvalid == 4) {
+            s4 t;
+            t.x = (short)j[0]; t.y = (short)j[1]; t.z = (short)j[2]; t.w = (short)j[3];
+            __builtin_nontemporal_store(t, reinterpret_cast<s4_a2*>(p));
+            return;
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) if (t < nvalid) p[t] = (int16_t)j[t];
+    }
+}
+
+// uniforms of four consecutive elements that start r into a Philox block: words r..3 of the block
+// of gi and words 0..r-1 of the next one
+__device__ __forceinline__ void uniforms_shifted(const StepScalars& S, int64_t gi, uint32_t worker, uint32_t stream,
+                                                 int r, float (&U)[4])
+{
+    float lo[4], hi[4];
+    uniforms<4>(S, gi - r, worker, stream, lo);
+    uniforms<4>(S, gi - r + 4, worker, stream, hi);
+    const bool r1 = r == 1, r2 = r == 2;
+    U[0] = r1 ? lo[1] : (r2 ? lo[2] : lo[3]);
+    U[1] = r1 ? lo[2] : (r2 ? lo[3] : hi[0]);
+    U[2] = r1 ? lo[3] : (r2 ? hi[0] : hi[1]);
+    U[3] = r1 ? hi[0] : (r2 ? hi[1] : hi[2]);
+}
+
+// the accessors of the tile loops: SH selects the shifted forms
+template <int V, bool SH>
+__device__ __forceinline__ void ld(const float* __restrict__ buf, int64_t gi, int nvalid, const Shift& sf, float (&out)[V])
+{
+    if constexpr (SH) load_shifted(buf + gi, nvalid, out);
+    else load_v<V>(buf + gi, nvalid, out);
+}
+
+template <int V, bool SH>
+__device__ __forceinline__ void st(float* __restrict__ buf, int64_t gi, int nvalid, const Shift& sf, const float (&in)[V])
+{
+    if constexpr (SH) store_shifted(buf + gi, nvalid, in);
+    else store_v<V>(buf + gi, nvalid, in);
+}
+
+template <int V, bool SH>
+__device__ __forceinline__ void stw(void* __restrict__ base, int wcode_bytes, int64_t gi, int nvalid, const Shift& sf,
+                                    const int (&j)[V])
+{
+    if constexpr (SH) store_wcodes_shifted(base, wcode_bytes, gi, nvalid, j);
+    else store_wcodes<V>(base, wcode_bytes, gi, nvalid, j);
+}
+
+template <int V, bool SH>
+__device__ __forceinline__ void unif(const StepScalars& S, int64_t gi, uint32_t worker, uint32_t stream, const Shift& sf,
+                                     float (&U)[V])
+{
+    if constexpr (SH) uniforms_shifted(S, gi, worker, stream, sf.r, U);
+    else uniforms<V>(S, gi, worker, stream, U);
+}
+
+// ------------------------------------------------------------------------------------------------
 // Server arithmetic on one lane: moments (Alg. 1, moment recursions) and the step alpha m / sqrt(v + eps).
 // ------------------------------------------------------------------------------------------------
 __device__ __forceinline__ float adam_step(const StepScalars& S, float gbar, float& m, float& v)
@@ -378,9 +495,9 @@ __device__ __forceinline__ void qx_value(float y, float two_kx1, float inv_two_k
     xhat = jf * inv_two_kx1;
 }
 
-template <int V, int ROUNDING>
+template <int V, int ROUNDING, bool SH = false>
 __device__ __forceinline__ void weight_lane(const StepScalars& S, const float (&x)[V], const float (&werr_in)[V],
-                                            int64_t gi, float (&werr_out)[V], int (&j)[V])
+                                            int64_t gi, const Shift& sf, float (&werr_out)[V], int (&j)[V])
 {
     const float two_kx1 = u2f((uint32_t)(127 + S.k_x + 1) << 23);
     const float inv = u2f((uint32_t)(127 - S.k_x - 1) << 23);
@@ -388,7 +505,7 @@ __device__ __forceinline__ void weight_lane(const StepScalars& S, const float (&
     float U[V];
 #pragma unroll
     for (int t = 0; t < V; ++t) U[t] = 0.0f;
-    if constexpr (ROUNDING == 1) uniforms<V>(S, gi, 0u, 1u, U);
+    if constexpr (ROUNDING == 1) unif<V, SH>(S, gi, 0u, 1u, sf, U);
 #pragma unroll
     for (int t = 0; t < V; ++t) {
         const float y = S.weight_ef ? x[t] + werr_in[t] : x[t];
@@ -513,6 +630,69 @@ __device__ __forceinline__ uint32_t block_max(uint32_t local)
 #pragma unroll
     for (int w = 1; w < kBlockThreads / 64; ++w) bm = wave_part[w] > bm ? wave_part[w] : bm;
     return bm;
+}
+
+// max |g + e| (g == null: max |e|) over the flat range [start, start + len) wherever it begins: a
+// maximum does not care which lane sees which element, so the range is walked as the aligned quads of
+// memory it contains plus at most three single elements at either end.  thr != 0: e is read only for
+// quads (elements) whose |g| reaches thr (filtered scale pass).
+template <bool STREAMING>
+__device__ __forceinline__ uint32_t amax_range(const float* __restrict__ g, const float* __restrict__ e,
+                                               int64_t start, int len, uint32_t thr)
+{
+    const int64_t end = start + len;
+    int64_t a0 = (start + 3) & ~(int64_t)3;
+    a0 = a0 < end ? a0 : end;
+    int64_t a1 = end & ~(int64_t)3;
+    a1 = a1 > a0 ? a1 : a0;
+    uint32_t local = 0;
+    const int head = (int)(a0 - start), tail = (int)(end - a1);
+    if ((int)threadIdx.x < head + tail) {
+        const int64_t idx = (int)threadIdx.x < head ? start + threadIdx.x : a1 + ((int)threadIdx.x - head);
+        const float gv = g ? g[idx] : 0.0f;
+        if (thr == 0u || (f2u(gv) & 0x7fffffffu) >= thr) {
+            const uint32_t ab = f2u(gv + e[idx]) & 0x7fffffffu;
+            local = ab;
+        }
+    }
+    // four quads per lane per trip, their loads issued together (a tile holds at most 1024 quads)
+    for (int64_t q0 = a0 + (int64_t)threadIdx.x * 4; q0 < a1; q0 += kBlockThreads * 16) {
+        float gv[4][4], ev[4][4];
+        bool live[4], cand[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int64_t q = q0 + (int64_t)k * kBlockThreads * 4;
+            live[k] = q < a1;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { gv[k][j] = 0.0f; ev[k][j] = 0.0f; }
+            if (live[k] && g) load_v<4, STREAMING>(g + q, 4, gv[k]);
+            if (live[k] && thr == 0u) load_v<4, STREAMING>(e + q, 4, ev[k]);
+        }
+        if (thr != 0u) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                uint32_t top = 0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t ab = f2u(gv[k][j]) & 0x7fffffffu;
+                    top = ab > top ? ab : top;
+                }
+                cand[k] = live[k] && top >= thr;
+                if (cand[k]) load_v<4, STREAMING>(e + q0 + (int64_t)k * kBlockThreads * 4, 4, ev[k]);
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if (thr == 0u ? live[k] : cand[k]) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t ab = f2u(gv[k][j] + ev[k][j]) & 0x7fffffffu;
+                    local = ab > local ? ab : local;
+                }
+            }
+        }
+    }
+    return local;
 }
 
 // ---- small layers: the scales are taken by the quantizing workgroup itself -----------------------
@@ -685,7 +865,7 @@ __global__ void __launch_bounds__(kBlockThreads) k_amax(AmaxArgs A)
     const float* g = A.grad[w];
     const float* e = A.err[w];
     uint32_t local;
-    if (t.flags & kTileUnaligned) local = amax_tile<1>(g, e, t);
+    if (t.flags & kTileUnaligned) local = amax_range<true>(g, e, t.start, t.len, 0u);
     else local = amax_tile<4>(g, e, t);
     const uint32_t bm = block_max(local);
     if (threadIdx.x == 0) A.tile_max[(size_t)w * A.num_tiles + ti] = bm;
@@ -760,13 +940,9 @@ __global__ void __launch_bounds__(kBlockThreads) k_amax_filtered(AmaxArgs A)
     const float* e = A.err[w];
     const uint32_t thr = A.thr[(size_t)w * A.num_segments + t.seg];
     uint32_t local;
-    if (thr == 0u) {
-        if (t.flags & kTileUnaligned) local = amax_tile<1>(g, e, t);
-        else local = amax_tile<4>(g, e, t);
-    } else {
-        if (t.flags & kTileUnaligned) local = amax_tile_filtered<1>(g, e, t, thr);
-        else local = amax_tile_filtered<4>(g, e, t, thr);
-    }
+    if (t.flags & kTileUnaligned) local = amax_range<true>(g, e, t.start, t.len, thr);
+    else if (thr == 0u) local = amax_tile<4>(g, e, t);
+    else local = amax_tile_filtered<4>(g, e, t, thr);
     const uint32_t bm = block_max(local);
     if (threadIdx.x == 0) A.tile_max[(size_t)w * A.num_tiles + ti] = bm;
 }
@@ -797,7 +973,7 @@ __global__ void __launch_bounds__(kBlockThreads) k_check_error_bounds(AmaxArgs A
     const Tile t = A.tiles[ti];
     const int w = A.first_worker + blockIdx.y;
     const float* e = A.err[w];
-    const uint32_t local = (t.flags & kTileUnaligned) ? emax_tile<1>(e, t) : emax_tile<4>(e, t);
+    const uint32_t local = (t.flags & kTileUnaligned) ? amax_range<true>(nullptr, e, t.start, t.len, 0u) : emax_tile<4>(e, t);
     const uint32_t bm = block_max(local);
     if (threadIdx.x == 0) {
         const float bound = A.err_bound[(size_t)w * A.num_segments + t.seg];
@@ -833,7 +1009,7 @@ __device__ __forceinline__ void store_chunk_words(uint32_t* __restrict__ codes, 
 }
 
 // ---- worker side alone (qadam_worker_quantize, second pass of variant W) -------------------------
-template <int V, int ROUNDING, bool PARKED, bool INLINE = false>
+template <int V, int ROUNDING, bool PARKED, bool INLINE = false, bool SH = false>
 __device__ __forceinline__ void worker_tile(const WorkerArgs& A, const Tile& t, const SmallLayerShared* sh = nullptr)
 {
     constexpr int WAVE_ELEMS = 64 * V, BLOCK_ELEMS = (kBlockThreads / 64) * WAVE_ELEMS;
@@ -843,6 +1019,7 @@ __device__ __forceinline__ void worker_tile(const WorkerArgs& A, const Tile& t, 
     const float s = INLINE ? sh->scale[0] : A.scales[t.seg];
     const float inv_s = INLINE ? sh->inv[0] : A.inv_scales[t.seg];
     if (!(s >= 0.0f && s < __builtin_inff()) && threadIdx.x == 0) atomicOr(A.status, QADAM_STATUS_NONFINITE_SCALE);
+    const Shift sf = make_shift(t);
     for (int base = wave * WAVE_ELEMS; base < t.len; base += BLOCK_ELEMS) {
         const int off = base + lane * V;
         const int nvalid = min(max(t.len - off, 0), V);
@@ -852,17 +1029,17 @@ __device__ __forceinline__ void worker_tile(const WorkerArgs& A, const Tile& t, 
         for (int j = 0; j < V; ++j) U[j] = 0.0f;
         if constexpr (PARKED) {
             // the first pass left p = u + e in the error buffer; p + 0 reproduces it
-            load_v<V>(A.err + gi, nvalid, g);
+            ld<V, SH>(A.err, gi, nvalid, sf, g);
 #pragma unroll
             for (int j = 0; j < V; ++j) e[j] = 0.0f;
         } else {
-            load_v<V>(A.grad + gi, nvalid, g);
-            load_v<V>(A.err + gi, nvalid, e);
+            ld<V, SH>(A.grad, gi, nvalid, sf, g);
+            ld<V, SH>(A.err, gi, nvalid, sf, e);
         }
-        if constexpr (ROUNDING == 1) uniforms<V>(S, gi, (uint32_t)A.worker, 0u, U);
+        if constexpr (ROUNDING == 1) unif<V, SH>(S, gi, (uint32_t)A.worker, 0u, sf, U);
         uint32_t codes;
         worker_lane<V, ROUNDING>(g, e, s, inv_s, c, S.mu_bits, U, q, en, codes);
-        store_v<V>(A.err + gi, nvalid, en);
+        st<V, SH>(A.err, gi, nvalid, sf, en);
         int slot; bool writes;
         const uint32_t word = pack_planes<V>(codes, S.code_bits, lane, slot, writes);
         store_chunk_words(A.codes, t, base, S.code_bits, word, slot, writes);
@@ -892,15 +1069,15 @@ __device__ __forceinline__ void worker_small_layer(const WorkerArgs& A, const Ti
     __shared__ SmallLayerShared sh;
     const int n = head.layer_len;
     const bool unaligned = head.flags & kTileUnaligned;
-    const uint32_t wm = unaligned ? small_layer_wave_max<1>(A.grad, A.err, head.start, n)
+    const uint32_t wm = unaligned ? wave_max_u32(amax_range<false>(A.grad, A.err, head.start, n, 0u))
                                   : small_layer_wave_max<4>(A.grad, A.err, head.start, n);
     if ((threadIdx.x & 63) == 0) sh.part[0][threadIdx.x >> 6] = wm;
     float* scales_row[1] = {A.scales};
     small_layer_finish(sh, 0, 1, head.seg, 1, scales_row, A.inv_scales, A.err_bound, A.bound_factor, true);
     for (int o = 0; o < n; o += kDefaultTileElems) {
         const Tile t = small_layer_tile(head, o, A.S.code_bits);
-        if (unaligned) worker_tile<1, ROUNDING, false, true>(A, t, &sh);
-        else worker_tile<4, ROUNDING, false, true>(A, t, &sh);
+        if (unaligned) worker_tile<4, ROUNDING, false, true, true>(A, t, &sh);
+        else worker_tile<4, ROUNDING, false, true, false>(A, t, &sh);
     }
 }
 
@@ -925,12 +1102,12 @@ __global__ void __launch_bounds__(kBlockThreads) k_worker_quantize(WorkerArgs A)
         if ((threadIdx.x & 63) == 0) sh.part[0][threadIdx.x >> 6] = wm;
         float* scales_row[1] = {A.scales};
         small_layer_finish(sh, 0, 1, t.seg, 1, scales_row, A.inv_scales, A.err_bound, A.bound_factor, true, ti == t0);
-        if (t.flags & kTileUnaligned) worker_tile<1, ROUNDING, PARKED, true>(A, t, &sh);
-        else worker_tile<4, ROUNDING, PARKED, true>(A, t, &sh);
+        if (t.flags & kTileUnaligned) worker_tile<4, ROUNDING, PARKED, true, true>(A, t, &sh);
+        else worker_tile<4, ROUNDING, PARKED, true, false>(A, t, &sh);
         return;
     }
-    if (t.flags & kTileUnaligned) worker_tile<1, ROUNDING, PARKED>(A, t);
-    else worker_tile<4, ROUNDING, PARKED>(A, t);
+    if (t.flags & kTileUnaligned) worker_tile<4, ROUNDING, PARKED, false, true>(A, t);
+    else worker_tile<4, ROUNDING, PARKED, false, false>(A, t);
 }
 
 // ---- server side alone (qadam_server_step) -------------------------------------------------------
@@ -946,13 +1123,14 @@ struct ServerArgs {
 
 // U = number of workers whose code words are loaded together (N must be a multiple of U);
 // MU_BITS = bits of the level index (code bits minus the sign)
-template <int V, int U, int MU_BITS>
+template <int V, int U, int MU_BITS, bool SH = false>
 __device__ __forceinline__ void server_tile(const ServerArgs& A, const Tile& t)
 {
     constexpr int WAVE_ELEMS = 64 * V, BLOCK_ELEMS = (kBlockThreads / 64) * WAVE_ELEMS;
     const StepScalars& S = A.S;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const QgConst c = make_qg(S.k_g);
+    const Shift sf = make_shift(t);
     for (int base = wave * WAVE_ELEMS; base < t.len; base += BLOCK_ELEMS) {
         const int off = base + lane * V;
         const int nvalid = min(max(t.len - off, 0), V);
@@ -961,10 +1139,10 @@ __device__ __forceinline__ void server_tile(const ServerArgs& A, const Tile& t)
         const int64_t cw = t.code_word + (int64_t)(base >> 5) * S.code_bits;
         // server state first: its latency hides behind the decoding
         float xv[V], mv[V], vv[V];
-        load_v<V>(A.x + gi, nvalid, xv);
+        ld<V, SH>(A.x, gi, nvalid, sf, xv);
         if (!A.apply_only) {
-            load_v<V>(A.m + gi, nvalid, mv);
-            load_v<V>(A.v + gi, nvalid, vv);
+            ld<V, SH>(A.m, gi, nvalid, sf, mv);
+            ld<V, SH>(A.v, gi, nvalid, sf, vv);
         }
         float acc[V];
 #pragma unroll
@@ -991,10 +1169,10 @@ __device__ __forceinline__ void server_tile(const ServerArgs& A, const Tile& t)
                 const float u = adam_step(S, mean_over_workers(S, acc[j]), mv[j], vv[j]);
                 xv[j] = xv[j] - u;
             }
-            store_v<V>(A.m + gi, nvalid, mv);
-            store_v<V>(A.v + gi, nvalid, vv);
+            st<V, SH>(A.m, gi, nvalid, sf, mv);
+            st<V, SH>(A.v, gi, nvalid, sf, vv);
         }
-        store_v<V>(A.x + gi, nvalid, xv);
+        st<V, SH>(A.x, gi, nvalid, sf, xv);
     }
 }
 
@@ -1003,8 +1181,8 @@ __global__ void __launch_bounds__(kBlockThreads) k_server_step(ServerArgs A)
 {
     const int ti = blockIdx.x;
     const Tile t = A.tiles[ti];
-    if (t.flags & kTileUnaligned) server_tile<1, 1, MU_BITS>(A, t);
-    else server_tile<4, U, MU_BITS>(A, t);
+    if (t.flags & kTileUnaligned) server_tile<4, U, MU_BITS, true>(A, t);
+    else server_tile<4, U, MU_BITS, false>(A, t);
 }
 
 // ---- weight quantizer alone (qadam_weight_quantize) ----------------------------------------------
@@ -1042,7 +1220,7 @@ __global__ void __launch_bounds__(kBlockThreads) k_weight_quantize(WeightArgs A)
         const int64_t gi = base + 4 * ((int64_t)threadIdx.x + kBlockThreads * k);
         float wo[4];
         int j[4];
-        weight_lane<4, ROUNDING>(S, xv[k], wi[k], gi, wo, j);
+        weight_lane<4, ROUNDING>(S, xv[k], wi[k], gi, Shift{}, wo, j);
         if (A.werr) store_v<4>(A.werr + gi, nvalid[k], wo);
         store_wcodes<4>(A.wcodes, S.wcode_bytes, gi, nvalid[k], j);
     }
@@ -1059,9 +1237,6 @@ struct DequantArgs {
 // A lane owns four pieces of E consecutive codes (E = 4 for fp32 output, 8 for binary16, so that an output
 // store is always 128 bits), piece k being elements E * (lane + 256 k) .. of the workgroup's 1024 E codes:
 // every store of a wavefront is one contiguous 1 KiB run and the four code loads are issued together.
-typedef uint32_t u4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u2 __attribute__((ext_vector_type(2)));
-
 template <bool HALF, int CODE_BYTES>
 __global__ void __launch_bounds__(kBlockThreads) k_weight_dequantize(DequantArgs A)
 {
@@ -1141,7 +1316,7 @@ __global__ void __launch_bounds__(kBlockThreads) k_weight_dequantize(DequantArgs
 // W = false: variant S (workers' g and e in, server moments).  W = true: second pass of variant W
 // (the first pass left p_i = alpha m_i / sqrt(v_i + eps) + e_i in the error buffers; the server
 // only subtracts the mean message).
-template <int V, int ROUNDING, int U, bool W, bool INLINE = false>
+template <int V, int ROUNDING, int U, bool W, bool INLINE = false, bool SH = false>
 __device__ __forceinline__ void fused_tile(const FusedArgs& A, const Tile& t, const SmallLayerShared* sh = nullptr)
 {
     constexpr int WAVE_ELEMS = 64 * V, BLOCK_ELEMS = (kBlockThreads / 64) * WAVE_ELEMS;
@@ -1149,6 +1324,7 @@ __device__ __forceinline__ void fused_tile(const FusedArgs& A, const Tile& t, co
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const QgConst c = make_qg(S.k_g);
     const int N = S.num_workers;
+    const Shift sf = make_shift(t);
     for (int base = wave * WAVE_ELEMS; base < t.len; base += BLOCK_ELEMS) {
         const int off = base + lane * V;
         const int nvalid = min(max(t.len - off, 0), V);
@@ -1158,13 +1334,13 @@ __device__ __forceinline__ void fused_tile(const FusedArgs& A, const Tile& t, co
         int jc[V];
 #pragma unroll
         for (int j = 0; j < V; ++j) wi[j] = 0.0f;
-        load_v<V>(A.sp.x + gi, nvalid, xv);
+        ld<V, SH>(A.sp.x, gi, nvalid, sf, xv);
         if constexpr (!W) {
-            load_v<V>(A.sp.m + gi, nvalid, mv);
-            load_v<V>(A.sp.v + gi, nvalid, vv);
+            ld<V, SH>(A.sp.m, gi, nvalid, sf, mv);
+            ld<V, SH>(A.sp.v, gi, nvalid, sf, vv);
         }
         const bool quantize_x = S.k_x >= 0;              // false: Q_x is the identity
-        if (S.weight_ef && quantize_x) load_v<V>(A.sp.werr + gi, nvalid, wi);
+        if (S.weight_ef && quantize_x) ld<V, SH>(A.sp.werr, gi, nvalid, sf, wi);
         float acc[V];
 #pragma unroll
         for (int j = 0; j < V; ++j) acc[j] = 0.0f;
@@ -1173,12 +1349,12 @@ __device__ __forceinline__ void fused_tile(const FusedArgs& A, const Tile& t, co
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 if constexpr (W) {
-                    load_v<V>(A.err[i0 + u] + gi, nvalid, g[u]);       // parked p; p + 0 reproduces it
+                    ld<V, SH>(A.err[i0 + u], gi, nvalid, sf, g[u]);       // parked p; p + 0 reproduces it
 #pragma unroll
                     for (int j = 0; j < V; ++j) e[u][j] = 0.0f;
                 } else {
-                    load_v<V>(A.grad[i0 + u] + gi, nvalid, g[u]);
-                    load_v<V>(A.err[i0 + u] + gi, nvalid, e[u]);
+                    ld<V, SH>(A.grad[i0 + u], gi, nvalid, sf, g[u]);
+                    ld<V, SH>(A.err[i0 + u], gi, nvalid, sf, e[u]);
                 }
             }
 #pragma unroll
@@ -1189,10 +1365,10 @@ __device__ __forceinline__ void fused_tile(const FusedArgs& A, const Tile& t, co
                 float q[V], en[V], Ur[V];
 #pragma unroll
                 for (int j = 0; j < V; ++j) Ur[j] = 0.0f;
-                if constexpr (ROUNDING == 1) uniforms<V>(S, gi, (uint32_t)i, 0u, Ur);
+                if constexpr (ROUNDING == 1) unif<V, SH>(S, gi, (uint32_t)i, 0u, sf, Ur);
                 uint32_t codes;
                 worker_lane<V, ROUNDING>(g[u], e[u], s, inv_s, c, S.mu_bits, Ur, q, en, codes);
-                store_v<V>(A.err[i] + gi, nvalid, en);
+                st<V, SH>(A.err[i], gi, nvalid, sf, en);
                 int slot; bool writes;
                 const uint32_t word = pack_planes<V>(codes, S.code_bits, lane, slot, writes);
                 store_chunk_words(A.codes[i], t, base, S.code_bits, word, slot, writes);
@@ -1212,14 +1388,14 @@ __device__ __forceinline__ void fused_tile(const FusedArgs& A, const Tile& t, co
             }
         }
         if constexpr (!W) {
-            store_v<V>(A.sp.m + gi, nvalid, mv);
-            store_v<V>(A.sp.v + gi, nvalid, vv);
+            st<V, SH>(A.sp.m, gi, nvalid, sf, mv);
+            st<V, SH>(A.sp.v, gi, nvalid, sf, vv);
         }
-        store_v<V>(A.sp.x + gi, nvalid, xv);
+        st<V, SH>(A.sp.x, gi, nvalid, sf, xv);
         if (quantize_x) {
-            weight_lane<V, ROUNDING>(S, xv, wi, gi, wo, jc);
-            if (A.sp.werr) store_v<V>(A.sp.werr + gi, nvalid, wo);
-            store_wcodes<V>(A.sp.wcodes, S.wcode_bytes, gi, nvalid, jc);
+            weight_lane<V, ROUNDING, SH>(S, xv, wi, gi, sf, wo, jc);
+            if (A.sp.werr) st<V, SH>(A.sp.werr, gi, nvalid, sf, wo);
+            stw<V, SH>(A.sp.wcodes, S.wcode_bytes, gi, nvalid, sf, jc);
         }
     }
     for (int i = 0; i < N; ++i) {
@@ -1239,15 +1415,15 @@ __device__ __forceinline__ void fused_small_layer(const FusedArgs& A, const Tile
     const int n = head.layer_len, N = A.S.num_workers;
     const bool unaligned = head.flags & kTileUnaligned;
     for (int i = 0; i < N; ++i) {
-        const uint32_t wm = unaligned ? small_layer_wave_max<1>(A.grad[i], A.err[i], head.start, n)
+        const uint32_t wm = unaligned ? wave_max_u32(amax_range<false>(A.grad[i], A.err[i], head.start, n, 0u))
                                       : small_layer_wave_max<4>(A.grad[i], A.err[i], head.start, n);
         if ((threadIdx.x & 63) == 0) sh.part[i][threadIdx.x >> 6] = wm;
     }
     small_layer_finish(sh, 0, N, head.seg, A.num_segments, A.scales, A.inv_scales, A.err_bound, A.bound_factor, false);
     for (int o = 0; o < n; o += kDefaultTileElems) {
         const Tile t = small_layer_tile(head, o, A.S.code_bits);
-        if (unaligned) fused_tile<1, ROUNDING, 1, false, true>(A, t, &sh);
-        else fused_tile<4, ROUNDING, U, false, true>(A, t, &sh);
+        if (unaligned) fused_tile<4, ROUNDING, U, false, true, true>(A, t, &sh);
+        else fused_tile<4, ROUNDING, U, false, true, false>(A, t, &sh);
     }
 }
 
@@ -1275,19 +1451,19 @@ __global__ void __launch_bounds__(kBlockThreads) k_fused(FusedArgs A)
         }
         small_layer_finish(sh, 0, N, t.seg, A.num_segments, A.scales, A.inv_scales, A.err_bound, A.bound_factor, false,
                            ti == t0);
-        if (t.flags & kTileUnaligned) fused_tile<1, ROUNDING, 1, W, true>(A, t, &sh);
-        else fused_tile<4, ROUNDING, U, W, true>(A, t, &sh);
+        if (t.flags & kTileUnaligned) fused_tile<4, ROUNDING, U, W, true, true>(A, t, &sh);
+        else fused_tile<4, ROUNDING, U, W, true, false>(A, t, &sh);
         return;
     }
-    if (t.flags & kTileUnaligned) fused_tile<1, ROUNDING, 1, W>(A, t);
-    else fused_tile<4, ROUNDING, U, W>(A, t);
+    if (t.flags & kTileUnaligned) fused_tile<4, ROUNDING, U, W, false, true>(A, t);
+    else fused_tile<4, ROUNDING, U, W, false, false>(A, t);
 }
 
 // ---- Q_g = identity: the messages are fp32 values ------------------------------------------------
 // W = false: the message of worker i is its gradient (plain distributed generic Adam on the mean
 // gradient, then Q_x).  W = true: second pass of variant W with the identity quantizer: the message
 // is the parked p_i = alpha m_i / sqrt(v_i + eps) + e_i, all of it is sent, so e_i <- 0.
-template <int V, int ROUNDING, int U, bool W>
+template <int V, int ROUNDING, int U, bool W, bool SH = false>
 __device__ __forceinline__ void plain_tile(const FusedArgs& A, const Tile& t)
 {
     constexpr int WAVE_ELEMS = 64 * V, BLOCK_ELEMS = (kBlockThreads / 64) * WAVE_ELEMS;
@@ -1295,6 +1471,7 @@ __device__ __forceinline__ void plain_tile(const FusedArgs& A, const Tile& t)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int N = S.num_workers;
     const bool quantize_x = S.k_x >= 0;
+    const Shift sf = make_shift(t);
     for (int base = wave * WAVE_ELEMS; base < t.len; base += BLOCK_ELEMS) {
         const int off = base + lane * V;
         const int nvalid = min(max(t.len - off, 0), V);
@@ -1304,24 +1481,24 @@ __device__ __forceinline__ void plain_tile(const FusedArgs& A, const Tile& t)
         int jc[V];
 #pragma unroll
         for (int j = 0; j < V; ++j) { wi[j] = 0.0f; acc[j] = 0.0f; zero[j] = 0.0f; }
-        load_v<V>(A.sp.x + gi, nvalid, xv);
+        ld<V, SH>(A.sp.x, gi, nvalid, sf, xv);
         if constexpr (!W) {
-            load_v<V>(A.sp.m + gi, nvalid, mv);
-            load_v<V>(A.sp.v + gi, nvalid, vv);
+            ld<V, SH>(A.sp.m, gi, nvalid, sf, mv);
+            ld<V, SH>(A.sp.v, gi, nvalid, sf, vv);
         }
-        if (S.weight_ef && quantize_x) load_v<V>(A.sp.werr + gi, nvalid, wi);
+        if (S.weight_ef && quantize_x) ld<V, SH>(A.sp.werr, gi, nvalid, sf, wi);
         for (int i0 = 0; i0 < N; i0 += U) {
             float p[U][V];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                if constexpr (W) load_v<V>(A.err[i0 + u] + gi, nvalid, p[u]);
-                else load_v<V>(A.grad[i0 + u] + gi, nvalid, p[u]);
+                if constexpr (W) ld<V, SH>(A.err[i0 + u], gi, nvalid, sf, p[u]);
+                else ld<V, SH>(A.grad[i0 + u], gi, nvalid, sf, p[u]);
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
 #pragma unroll
                 for (int j = 0; j < V; ++j) acc[j] = acc[j] + p[u][j];
-                if constexpr (W) store_v<V>(A.err[i0 + u] + gi, nvalid, zero);
+                if constexpr (W) st<V, SH>(A.err[i0 + u], gi, nvalid, sf, zero);
             }
         }
         if constexpr (W) {
@@ -1333,14 +1510,14 @@ __device__ __forceinline__ void plain_tile(const FusedArgs& A, const Tile& t)
                 const float u = adam_step(S, mean_over_workers(S, acc[j]), mv[j], vv[j]);
                 xv[j] = xv[j] - u;
             }
-            store_v<V>(A.sp.m + gi, nvalid, mv);
-            store_v<V>(A.sp.v + gi, nvalid, vv);
+            st<V, SH>(A.sp.m, gi, nvalid, sf, mv);
+            st<V, SH>(A.sp.v, gi, nvalid, sf, vv);
         }
-        store_v<V>(A.sp.x + gi, nvalid, xv);
+        st<V, SH>(A.sp.x, gi, nvalid, sf, xv);
         if (quantize_x) {
-            weight_lane<V, ROUNDING>(S, xv, wi, gi, wo, jc);
-            if (A.sp.werr) store_v<V>(A.sp.werr + gi, nvalid, wo);
-            store_wcodes<V>(A.sp.wcodes, S.wcode_bytes, gi, nvalid, jc);
+            weight_lane<V, ROUNDING, SH>(S, xv, wi, gi, sf, wo, jc);
+            if (A.sp.werr) st<V, SH>(A.sp.werr, gi, nvalid, sf, wo);
+            stw<V, SH>(A.sp.wcodes, S.wcode_bytes, gi, nvalid, sf, jc);
         }
     }
 }
@@ -1350,8 +1527,8 @@ __global__ void __launch_bounds__(kBlockThreads) k_plain_messages(FusedArgs A)
 {
     const int ti = blockIdx.x;
     const Tile t = A.tiles[ti];
-    if (t.flags & kTileUnaligned) plain_tile<1, ROUNDING, 1, W>(A, t);
-    else plain_tile<4, ROUNDING, U, W>(A, t);
+    if (t.flags & kTileUnaligned) plain_tile<4, ROUNDING, U, W, true>(A, t);
+    else plain_tile<4, ROUNDING, U, W, false>(A, t);
 }
 
 // ---- variant W, first pass: local moments, park p = u + e in the error buffer, scale ------------
@@ -1367,21 +1544,23 @@ struct MomentsWArgs {
     int first_worker;
 };
 
-template <int V>
+template <int V, bool SH = false>
 __device__ __forceinline__ uint32_t moments_w_tile(const StepScalars& S, const float* __restrict__ grad,
                                                    float* __restrict__ mw, float* __restrict__ vw,
                                                    float* __restrict__ err, const Tile& t)
 {
     constexpr int BLOCK_ELEMS = kBlockThreads * V;
     uint32_t local = 0;
-    for (int off = threadIdx.x * V; off < t.len; off += BLOCK_ELEMS) {
-        const int nvalid = min(t.len - off, V);
+    const Shift sf = make_shift(t);
+    for (int base = 0; base < t.len; base += BLOCK_ELEMS) {
+        const int off = base + threadIdx.x * V;
+        const int nvalid = min(max(t.len - off, 0), V);
         const int64_t gi = t.start + off;
         float g[V], mv[V], vv[V], e[V], p[V];
-        load_v<V>(grad + gi, nvalid, g);
-        load_v<V>(mw + gi, nvalid, mv);
-        load_v<V>(vw + gi, nvalid, vv);
-        load_v<V>(err + gi, nvalid, e);
+        ld<V, SH>(grad, gi, nvalid, sf, g);
+        ld<V, SH>(mw, gi, nvalid, sf, mv);
+        ld<V, SH>(vw, gi, nvalid, sf, vv);
+        ld<V, SH>(err, gi, nvalid, sf, e);
 #pragma unroll
         for (int j = 0; j < V; ++j) {
             const float u = adam_step(S, g[j], mv[j], vv[j]);
@@ -1389,9 +1568,9 @@ __device__ __forceinline__ uint32_t moments_w_tile(const StepScalars& S, const f
             const uint32_t ab = j < nvalid ? (f2u(p[j]) & 0x7fffffffu) : 0u;
             local = ab > local ? ab : local;
         }
-        store_v<V>(mw + gi, nvalid, mv);
-        store_v<V>(vw + gi, nvalid, vv);
-        store_v<V>(err + gi, nvalid, p);
+        st<V, SH>(mw, gi, nvalid, sf, mv);
+        st<V, SH>(vw, gi, nvalid, sf, vv);
+        st<V, SH>(err, gi, nvalid, sf, p);
     }
     return local;
 }
@@ -1403,8 +1582,8 @@ __global__ void __launch_bounds__(kBlockThreads) k_moments_w(MomentsWArgs A)
     const Tile t = A.tiles[ti];
     const int w = A.first_worker + blockIdx.y;
     uint32_t local;
-    if (t.flags & kTileUnaligned) local = moments_w_tile<1>(A.S, A.grad[w], A.mw[w], A.vw[w], A.err[w], t);
-    else local = moments_w_tile<4>(A.S, A.grad[w], A.mw[w], A.vw[w], A.err[w], t);
+    if (t.flags & kTileUnaligned) local = moments_w_tile<4, true>(A.S, A.grad[w], A.mw[w], A.vw[w], A.err[w], t);
+    else local = moments_w_tile<4, false>(A.S, A.grad[w], A.mw[w], A.vw[w], A.err[w], t);
     const uint32_t bm = block_max(local);
     if (threadIdx.x == 0) A.tile_max[(size_t)w * A.num_tiles + ti] = bm;
 }

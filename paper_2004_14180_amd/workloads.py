@@ -199,9 +199,18 @@ class Workload:
             raise ValueError("unknown config %r" % self.config)
 
 
-def make_workload(config: int, shrink: int = 1, seed: int = 0) -> Workload:
+def make_workload(config: int, shrink: int = 1, seed: int = 0, misalign: bool = False) -> Workload:
     """The configuration `config` (1..5).  shrink > 1 divides the model dimensions (not the number
-    of layers) for quick parity runs that keep the layer structure."""
+    of layers) for quick parity runs that keep the layer structure.  misalign: put one 1001-element
+    layer in front, so that every layer of the configuration starts off a 16-byte boundary (the odd
+    layer itself is aligned; everything behind it starts at flat index = 1 mod 4)."""
+    if misalign:
+        wl = make_workload(config, shrink=shrink, seed=seed)
+        wl.sizes = [1001] + wl.sizes
+        wl.name += "+odd-first-layer"
+        if wl.embedding_rows:
+            wl.embedding_rows = 0      # the zeroed-row pattern addresses the first segment: not used here
+        return wl
     if config == 1:
         return Workload(1, "flat-1M", [max(1, (1 << 20) // shrink)], 1, 10, k_g=2, weight_quant=False,
                         weight_ef=0, seed=seed)

@@ -235,13 +235,15 @@ class FullRun:
                 f.result()
 
 
-def run_full_schedule(config, start_state):
+def run_full_schedule(config, start_state, misalign=False, steps=None):
     """The configuration's whole schedule at full size, every element compared after every step."""
-    wl = make_workload(config)
+    wl = make_workload(config, misalign=misalign)
+    if steps is not None:
+        wl.steps = steps
     run = FullRun(wl, start_state=start_state)
     run.init_host_state()
     rep = Report()
-    tag = "config%d full" % config
+    tag = "config%d full%s" % (config, " misaligned" if misalign else "")
     for t in range(1, wl.steps + 1):
         wl.fill_gradients(t, run.grads)
         run.step(t)
@@ -272,3 +274,10 @@ def test_config5_gpt13b_full_size_all_5_steps():
     and launch configuration), from a synthetic mid-training state so that the first step already
     exercises every buffer: its 5 steps, every layer on every step."""
     run_full_schedule(5, "synthetic")
+
+
+def test_config5_gpt13b_full_size_off_alignment():
+    """Config 5 at full size behind one 1001-element layer, so that every one of its 292 layers starts at
+    a flat index = 1 mod 4 (the kernels then use their dword-aligned wide accesses everywhere): two steps,
+    the second with the filtered scale pass, every layer and every element."""
+    run_full_schedule(5, "synthetic", misalign=True, steps=2)

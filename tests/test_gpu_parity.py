@@ -68,6 +68,29 @@ def test_config5_gpt13b_shrunk():
     assert rep.ok()
 
 
+@pytest.mark.parametrize("fused", [True, False])
+def test_config5_shrunk_with_every_layer_off_alignment(fused):
+    """Config 5's layer list (dims / 8) behind one 1001-element layer: every layer then starts at a flat
+    index = 1 mod 4, so every kernel takes its shifted (lane-to-lane) access path on full-size tiles."""
+    wl = make_workload(5, shrink=8, misalign=True)
+    assert all(o % 4 == 1 for o in wl.seg_offsets[1:-1])
+    rep = run_workload_parity(wl, wl.steps, fused=fused, gen_device="cuda", trust_errs=fused)
+    _say("config5/8 misaligned fused=%s: %s" % (fused, rep.line()))
+    assert rep.ok()
+
+
+@pytest.mark.parametrize("shift", [1, 2, 3])
+@pytest.mark.parametrize("cfgkw", [dict(k_g=2, k_x=6), dict(k_g=0, k_x=14), dict(k_g=5, k_x=6, rounding=1, seed=3)])
+def test_every_misalignment_and_code_width(shift, cfgkw):
+    """Segments that start 1, 2 and 3 elements off a 16-byte boundary, with ragged ends, for 2-, 3- and 4-bit
+    gradient codes, int8 and int16 weight codes, nearest and stochastic rounding (whose random stream is
+    indexed by the flat element number, so it must shift with the data)."""
+    sizes = [shift, 4096 * 2 + 5, 33, 20000 - shift, 4096, 7, 70001]
+    for fused in (True, False):
+        rep, st = _custom(sizes, 3, 3, seed=70 + shift, cfgkw=cfgkw, fused=fused, trust=2 if fused else 0)
+        assert rep.ok() and st == 0, (shift, cfgkw, fused)
+
+
 # ------------------------------------------------------------------------------------- edge cases
 RAGGED = [1, 3, 31, 33, 0, 255, 257, 4095, 4097, 5000, 0, 64, 8192, 2, 12289, 7]
 

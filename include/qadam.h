@@ -38,9 +38,22 @@
  *   - The parameter vector is flat, P = seg_offsets[L] elements, split into L layer segments
  *     [seg_offsets[l], seg_offsets[l+1]); empty segments are allowed.
  *   - `step` is the 1-based iteration t.
- *   - Return value: QADAM_OK or a negative error code; on error nothing was enqueued.
+ *   - Return value: QADAM_OK or a negative error code.  QADAM_EINVAL, QADAM_EALIGN and QADAM_ERANGE come from
+ *     checks made before anything is enqueued: the buffers are untouched.  QADAM_EHIP means a kernel launch
+ *     was refused by the runtime part way through the call: launches accepted before it still run, so the
+ *     buffers of the call are then in an intermediate state (variant S: scales written, state not yet
+ *     advanced; variant W: m_i, v_i already advanced and the error buffers holding the parked
+ *     alpha_t m_i / sqrt(v_i + eps) + e_i instead of e_i) and the step cannot be repeated on them.
  *     Non-finite scales (NaN/Inf in g + e) are data errors: they set a bit in the status word that
  *     qadam_get_status reads; the outputs of that layer are then unspecified (codes stay in range).
+ *   - HIP graphs: the compute calls may be recorded into a graph (stream capture).  A replay repeats the
+ *     call with the arguments it was recorded with: the same pointers, and the same step, lr and beta2.
+ *     With nearest rounding and the paper's Adam (adam_flavor = 0) the step number enters no kernel, so a
+ *     replay stands for any iteration with that lr and beta2.  The calls return QADAM_EINVAL when asked to
+ *     record what a replay cannot follow: rounding = 1 (the random stream is keyed on the step) and
+ *     adam_flavor = 1 (bias corrections depend on the step).  A recorded call always uses the full scale
+ *     pass, whatever qadam_trust_error_buffers says, and a handle whose graph is being replayed should
+ *     not also run eager steps with that option on (replays rewrite the handle's residual bounds).
  *   - The library allocates only in qadam_init (tables proportional to P/4096 plus the segment
  *     table) and frees in qadam_destroy.
  *
@@ -114,20 +127,22 @@ typedef struct {
     uint32_t reserved;
 } qadam_status_t;
 
-/* Create a handle for one flat parameter vector.  seg_offsets: L+1 non-decreasing HOST values with
- * seg_offsets[0] = 0; num_workers in 1..QADAM_MAX_WORKERS.  Allocates the handle's device tables on
- * the current device. */
+/* Create a handle for one flat parameter vector x in R^d (Sec. 3, problem statement; state of Alg. 1 and
+ * of Alg. 2-3), split into the layers over which the norm of Q_g (Sec. 5.1) is taken.  seg_offsets: L+1
+ * non-decreasing HOST values with seg_offsets[0] = 0; num_workers = N of Alg. 2-3, in 1..QADAM_MAX_WORKERS.
+ * Allocates the handle's device tables on the current device. */
 int qadam_init(qadam_handle_t* out, const qadam_config_t* cfg,
                const int64_t* seg_offsets, int32_t num_segments, int32_t num_workers);
 int qadam_destroy(qadam_handle_t h);
 
-/* Bytes of one worker's packed gradient codes for the whole vector (including segment padding),
- * and of the weight codes. */
+/* Bytes of one worker's packed gradient codes for the whole vector (including segment padding), and of the
+ * weight codes: the message and model sizes of Tables 1-2 (b bits and 8 or 16 bits per element). */
 size_t qadam_grad_code_bytes(qadam_handle_t h);
 size_t qadam_weight_code_bytes(qadam_handle_t h);
 int64_t qadam_num_params(qadam_handle_t h);
 
-/* Worker side (steps p = g+e, s = ||p||_inf per layer, Q_g, residual):
+/* Worker side: the send and residual steps of Alg. 3 (update and residual steps of Alg. 1) applied to the
+ * gradient, with Q_g of Sec. 5.1 -- p = g + e, s = ||p||_inf per layer, codes of Q_g(p), e <- p - Q_g(p):
  *   grad_dev   [P] in        stochastic gradient g_i
  *   err_dev    [P] in/out    e_i -> p - Q_g(p)
  *   codes_dev  out           packed codes, qadam_grad_code_bytes bytes
@@ -157,20 +172,24 @@ int qadam_worker_quantize(qadam_handle_t h, int32_t worker, int64_t step,
 int qadam_quantize_segment_noalloc(int32_t k_g, int64_t n, const float* grad_dev, float* err_dev,
                                    void* codes_dev, float* scale_dev, void* stream);
 
-/* Server side (mean of the dequantized messages in worker order, moments, parameter step):
+/* Server side: the gather step of Alg. 2 (mean of the dequantized messages, in worker order), then the
+ * moment recursions and the update step of Alg. 1 on that mean (no quantizer in the update: Q_g acted on
+ * the worker):
  *   codes[i], scales[i]: worker i's outputs of qadam_worker_quantize, i = 0..N-1 (HOST arrays of
  *   device pointers);  x, m, v [P] in/out.  lr = alpha_t, beta2 = theta_t. */
 int qadam_server_step(qadam_handle_t h, int64_t step, float lr, float beta2,
                       const void* const* codes, const float* const* scales,
                       float* x_dev, float* m_dev, float* v_dev, void* stream);
 
-/* Weight quantizer Q_x with its residual:
+/* Weight quantizer Q_x of Sec. 5.1 with its residual; what the broadcast and output steps of Alg. 2 emit,
+ * Q_x(x_t), while the server keeps x_t:
  *   x_dev [P] in;  werr_dev [P]: in/out when weight_ef = 1, out only when 0 (may then be NULL);
  *   wcodes_dev out, qadam_weight_code_bytes bytes. */
 int qadam_weight_quantize(qadam_handle_t h, int64_t step, const float* x_dev,
                           float* werr_dev, void* wcodes_dev, void* stream);
 
-/* The whole step in one call: identical results, bit for bit, to qadam_worker_quantize for
+/* The whole step in one call (Alg. 3 send/residual steps for every worker, Alg. 2 gather step, Alg. 1
+ * moment and update steps, Q_x of Sec. 5.1): identical results, bit for bit, to qadam_worker_quantize for
  * i = 0..N-1, then qadam_server_step, then qadam_weight_quantize, but each buffer makes one trip
  * through memory in the main kernel (the scales need one earlier read of g and e).
  * grads, errs, codes, scales: HOST arrays of N device pointers. */
@@ -180,7 +199,9 @@ int qadam_step_fused(qadam_handle_t h, int64_t step, float lr, float beta2,
                      float* x_dev, float* m_dev, float* v_dev,
                      float* werr_dev, void* wcodes_dev, void* stream);
 
-/* Variant W (Algorithms 2-3 as printed): the worker owns m_i, v_i and quantizes
+/* Variant W (Algorithms 2-3 as printed; Alg. 1 for N = 1): the worker owns m_i, v_i (moment steps of
+ * Alg. 3) and quantizes its update (send step of Alg. 3); the server applies x <- x - mean (update step of
+ * Alg. 2, with the sign of Alg. 1).  The worker quantizes
  * alpha_t m_i / sqrt(v_i + eps) + e_i; the server subtracts the mean of the messages.
  *   qadam_worker_step_w: grad [P] in; mw, vw [P] in/out; err [P] in/out; codes, scales out.
  *   qadam_server_apply_w: x [P] in/out from the N messages. */
@@ -199,7 +220,8 @@ int qadam_step_fused_w(qadam_handle_t h, int64_t step, float lr, float beta2,
                        float* const* errs, void* const* codes, float* const* scales,
                        float* x_dev, float* werr_dev, void* wcodes_dev, void* stream);
 
-/* Dequantize weight codes (what a worker does with the broadcast of Alg. 2): x^ = j * 2^-(k_x+1).
+/* Dequantize weight codes (the receive step of Alg. 3: what a worker does with the broadcast of Alg. 2;
+ * grid X of Sec. 5.1): x^ = j * 2^-(k_x+1).
  *   qadam_weight_dequantize      xhat_dev [P] fp32, exact.
  *   qadam_weight_dequantize_f16  xhat_dev [P] IEEE binary16 (2 bytes per element, 16-byte aligned), for
  *                                a consumer that computes in half precision; exact for k_x <= 10,
@@ -217,8 +239,9 @@ int qadam_weight_dequantize_f16(qadam_handle_t h, const void* wcodes_dev, void* 
  * that lower bound and then reads e only where |g| is large enough to matter; the scales (and so every
  * output) are the same bits as without the option.  On Gaussian-like gradients this halves the scale
  * pass; on heavy-tailed ones it falls back to reading everything, layer by layer.
- * CONTRACT with the option on: between two step calls the caller must not change errs[i] (or must call this
- * function again, which makes the next step read everything).  The first step after qadam_init, or after
+ * CONTRACT with the option on: between two step calls the caller must not change the contents of errs[i] (or
+ * must call this function again, which makes the next step read everything).  Passing ANOTHER buffer for a
+ * worker than the one its bound was recorded for is noticed (the pointer is remembered) and gets the full pass.  The first step after qadam_init, or after
  * this call, always reads everything.  Violating the contract gives scales that are too small.
  * on = 1 uses the filtered pass only where it pays (it adds two small launches: from about
  * 10^8 worker-elements per call on); on = 2 uses it always; on = 0 (the default) never.
@@ -259,7 +282,10 @@ int qadam_arena_layout(qadam_handle_t h, size_t arena_bytes, int32_t with_worker
  * empirical ||p - Q_g(p)||^2 / ||p||^2 of Assumption 2 (must stay below 1). */
 int qadam_layer_sumsq(qadam_handle_t h, const float* a_dev, const float* b_dev, double* out_dev, void* stream);
 
-/* Read (and optionally clear) the status word.  Synchronises the given stream. */
+/* Read (and optionally clear) the status word.  The read and the clear are enqueued on `stream` and the call
+ * waits for that stream, so they are ordered against this stream's kernels; if the handle has work on other
+ * streams (per-worker calls), wait for those streams first, or a bit set there concurrently can be lost by
+ * the clear. */
 int qadam_get_status(qadam_handle_t h, qadam_status_t* out, int32_t clear, void* stream);
 
 /* Kernel timing for measurements.  When enabled, qadam_step_fused (and qadam_step_fused_w) bracket their two passes with HIP

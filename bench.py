@@ -37,14 +37,14 @@ KERNEL_SOURCE = os.path.join(ROOT, "paper_2004_14180_amd", "csrc", "qadam_kernel
 TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "fused_step_gpt1p3b_pmc_traffic.txt")
 
 
-def measured_traffic_bytes():
-    """HBM bytes per launch of the fused main pass on the headline workload, as the rocprofv3 counter
-    summary under profiles/ records them -- only if that summary was taken from the kernel source that is
-    being timed now (it stores the source's SHA-256); otherwise None."""
+def measured_traffic_bytes(key="k_fused_traffic_bytes_per_launch"):
+    """HBM bytes of the headline workload's kernels as the rocprofv3 counter summary under profiles/ records
+    them (per launch of the fused main pass; per step for the scale pass) -- only if that summary was taken
+    from the kernel source that is being timed now (it stores the source's SHA-256); otherwise None."""
     try:
         text = open(TRAFFIC_PROFILE).read()
         m_sha = re.search(r"^kernel_source_sha256:\s*([0-9a-f]{64})", text, re.M)
-        m_val = re.search(r"^k_fused_traffic_bytes_per_launch:\s*([0-9.eE+]+)", text, re.M)
+        m_val = re.search(r"^%s:\s*([0-9.eE+]+)" % re.escape(key), text, re.M)
         if not m_sha or not m_val:
             return None
         if hashlib.sha256(open(KERNEL_SOURCE, "rb").read()).hexdigest() != m_sha.group(1):
@@ -483,6 +483,8 @@ def run_fused(args, config, dev, steps, warmup, placement, headline):
         is_headline_cfg = (headline and args.shrink == 1 and args.k_g is None and args.k_x is None
                            and args.rounding == 0 and config == 5)
         traffic = measured_traffic_bytes() if is_headline_cfg else None
+        scale_traffic = measured_traffic_bytes("filtered_scale_pass_traffic_bytes_per_step" if filtered else
+                                               "full_scale_pass_traffic_bytes_per_step") if is_headline_cfg else None
         roofline = {"bound": "hbm", "kernel": "k_fused (main pass of qadam_step_fused)",
                     "scope": "this kernel's launches only; whole_step below covers the scale pass as well",
                     "achieved": gbs(a_main, main_avg), "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -493,7 +495,10 @@ def run_fused(args, config, dev, steps, warmup, placement, headline):
                     "algorithmic_bytes_per_param": a_main, "avg_launch_ms": round(main_avg, 4),
                     "scale_pass": {"mode": "filtered" if filtered else "full",
                                    "algorithmic_bytes_per_param": a_scale, "avg_launch_ms": round(scale_avg, 4),
-                                   "achieved": gbs(a_scale, scale_avg)},
+                                   "achieved": gbs(a_scale, scale_avg),
+                                   # HBM bytes of the pass per step by the same counters (filtered: g of every
+                                   # element, the sampled tiles and the few e that can matter)
+                                   "traffic": scale_traffic},
                     # bytes the step moves by design (main pass + scale pass) over the step's wall time
                     "whole_step": {"bytes_per_param": a_main + a_scale, "GBs": gbs(a_main + a_scale, ms_per_step),
                                    "frac": round(gbs(a_main + a_scale, ms_per_step) / HBM_PEAK_GBS, 4)},

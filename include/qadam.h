@@ -252,14 +252,14 @@ int qadam_trust_error_buffers(qadam_handle_t h, int32_t on);
 
 /* Placement of a handle's buffers inside ONE caller-allocated block (host arithmetic only; nothing is
  * allocated, no HIP call is made).  Why: the main pass of qadam_step_fused reads 2N+4 and writes N+5 streams at
- * once, and on MI355X its speed depends on where those streams lie in physical memory: when all of them fall
- * into the same 96 GiB third of the device's memory (what a process gets when it allocates its buffers one
- * after the other on a freshly booted GPU) the pass runs 8-10 % slower than when they are spread over at
- * least two thirds.  A block obtained with one hipMalloc on an otherwise empty device is physically
- * contiguous, so offsets inside it decide the placement: the layout puts every second buffer of each kind in
- * the first half of the block and the others in its second half.  The block should therefore be much larger
- * than the buffers (ideally most of the device's memory; the space between the two groups stays free for
- * the caller's other data).  Results never depend on placement, only speed does.
+ * once, and on MI355X its speed depends on where those streams lie in physical memory: with the buffers
+ * packed closely one after the other (what a process gets when it allocates them in turn on a freshly booted
+ * GPU) the pass runs 8-14 % slower than with the streams spread widely over the device's memory.  A block
+ * obtained with one hipMalloc on an otherwise empty device is physically contiguous, so offsets inside it
+ * decide the placement: the layout deals the buffers of each kind alternately to the first half of the block
+ * and to its second half.  The block should therefore be much larger than the buffers (ideally most of the
+ * device's memory; the space between the two groups stays free for the caller's other data).  Results never
+ * depend on placement, only speed does.
  *   arena_bytes   size of the caller's block; its base must be 256-byte aligned
  *   with_worker_moments  non-zero: also place mw[i], vw[i] (variant W)
  *   out           byte offsets from the block's base, each a multiple of 256: x, m, v, werr [4P bytes each],

@@ -82,7 +82,12 @@ class Buffers:
             # as large as the device allows (the two groups of buffers then lie far apart), leaving room
             # for the generator's temporaries
             arena_bytes = max(need, free_b - reserve_bytes)
-            self.arena = torch.empty(arena_bytes, dtype=torch.uint8, device=dev)
+            try:
+                self.arena = torch.empty(arena_bytes, dtype=torch.uint8, device=dev)
+            except RuntimeError:                      # the device cannot give one block of that size
+                torch.cuda.empty_cache()
+                placement = self.placement = "separate (one block of %d bytes was refused)" % arena_bytes
+        if self.arena is not None:
             lay = q.arena_layout(arena_bytes, variant_w)
             self.arena_bytes = arena_bytes
             f32 = lambda off, n: self.arena[off:off + 4 * n].view(torch.float32)
@@ -612,7 +617,7 @@ def main():
                    "worker_elements_per_s": r["worker_elements"],
                    "resident_bytes": r["resident"],
                    "placement": ("one allocation of %d bytes, offsets from qadam_arena_layout" % r["arena_bytes"])
-                   if args.placement == "arena" else
+                   if r["arena_bytes"] else
                    ("one allocation per buffer, %d allocator conditioning cycles" % args.alloc_cycles),
                    "hip_graph_replay": bool(args.graph),
                    "scale_pass": "filtered: exact scales, e read only where |g| can reach the layer maximum "

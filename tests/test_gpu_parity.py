@@ -1,7 +1,8 @@
 """GPU parity: the HIP library (through its C boundary) against the CPU oracle, element by element,
 on the seeded synthetic workloads and on edge cases.  Sizes are chosen so the oracle finishes in
 seconds while every tile shape occurs: full 4096-element tiles, ragged tails, segments that start
-off a 16-byte boundary (scalar path), tiny and empty segments."""
+off a 16-byte boundary (dword-aligned wide accesses), tiny and empty segments, small layers (one
+workgroup, no scale pass) and layers whose tile maxima the quantizing kernel folds itself."""
 import numpy as np
 import pytest
 import torch

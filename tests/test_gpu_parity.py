@@ -92,6 +92,29 @@ def test_every_misalignment_and_code_width(shift, cfgkw):
         assert rep.ok() and st == 0, (shift, cfgkw, fused)
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_random_layer_lists_and_settings(seed):
+    """Seeded random layer lists (empty, tiny, odd and tile-multiple sizes, so every alignment and every
+    kind of layer -- small, folded-by-the-quantizer, large -- occurs in changing order) under random
+    settings of N, k_g, k_x, rounding, weight feedback, fused or separate calls, filtered scale pass."""
+    rng = np.random.default_rng(1000 + seed)
+    pool = [0, 1, 2, 3, 5, 31, 32, 33, 64, 255, 1000, 1001, 4095, 4096, 4097, 8192, 12289, 16384, 16385, 20000,
+            4096 * 7 + 2, 65536, 100003]
+    sizes = [int(rng.choice(pool)) for _ in range(int(rng.integers(1, 9)))]
+    if rng.random() < 0.3:
+        sizes.append(4096 * 641 + int(rng.integers(0, 5)))      # a layer of more than 640 tiles
+    if sum(sizes) == 0:
+        sizes.append(7)
+    N = int(rng.choice([1, 2, 3, 4, 5, 8]))
+    cfgkw = dict(k_g=int(rng.integers(0, 7)), k_x=int(rng.choice([0, 3, 6, 7, 10, 14])),
+                 rounding=int(rng.integers(0, 2)), weight_ef=int(rng.integers(0, 2)), seed=int(rng.integers(0, 1 << 30)))
+    fused = bool(rng.integers(0, 2))
+    trust = int(rng.choice([0, 2]))
+    rep, st = _custom(sizes, N, 3, seed=2000 + seed, cfgkw=cfgkw, fused=fused, trust=trust,
+                      scale=float(10.0 ** rng.uniform(-4, 0)))
+    assert rep.ok() and st == 0 and rep.float_not_bit_exact == 0, (sizes, N, cfgkw, fused, trust, rep.line())
+
+
 # ------------------------------------------------------------------------------------- edge cases
 RAGGED = [1, 3, 31, 33, 0, 255, 257, 4095, 4097, 5000, 0, 64, 8192, 2, 12289, 7]
 

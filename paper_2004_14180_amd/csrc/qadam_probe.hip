@@ -7,7 +7,8 @@
 //   streams    R read-only + U updated-in-place (+ small write-only) fp32 streams walked in lockstep,
 //              one 16 KiB tile of every stream per workgroup, 128-bit non-temporal accesses:
 //              the shape of the scale pass (R = 16, U = 0) and of the fused main pass
-//              (R = 8 gradients, U = 12: errors, x, m, v, weight residual; codes as small writes)
+//              (R = 8 gradients, U = 12: errors, x, m, v, weight residual; codes as small writes);
+//              then the write-heavy shapes of the code utilities (pure fill, 1 byte in per 4 bytes out)
 //   placement  the main-pass shape again with its 20 buffers carved out of ONE allocation that spans the
 //              device's memory: packed back to back from different offsets, and dealt alternately to the
 //              two halves of the block -- where the buffers lie physically changes the rate by ~20 %
@@ -69,6 +70,8 @@ struct StreamArgs {
 };
 
 // one workgroup = one tile of 4096 elements of every stream; a lane owns 4 x 4 consecutive floats
+template <bool NT_STORE>
+__global__ void __launch_bounds__(256) k_streams_t(StreamArgs A);
 __global__ void __launch_bounds__(256) k_streams(StreamArgs A)
 {
     const size_t base = (size_t)blockIdx.x * 4096 + threadIdx.x * 4;
@@ -104,6 +107,58 @@ __global__ void __launch_bounds__(256) k_streams(StreamArgs A)
     }
 }
 
+template <bool NT_STORE>
+__global__ void __launch_bounds__(256) k_streams_t(StreamArgs A)
+{
+    const size_t base = (size_t)blockIdx.x * 4096 + threadIdx.x * 4;
+    f4 acc[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) acc[k] = f4{0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < A.n_ro; ++s) {
+        f4 v[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v[k] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(A.ro[s] + base + k * 1024));
+#pragma unroll
+        for (int k = 0; k < 4; ++k) acc[k] += v[k];
+    }
+    for (int s = 0; s < A.n_rw; ++s) {
+        f4 v[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v[k] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(A.rw[s] + base + k * 1024));
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            acc[k] += v[k];
+            if (NT_STORE) __builtin_nontemporal_store(acc[k] * 0.5f, reinterpret_cast<f4*>(A.rw[s] + base + k * 1024));
+            else *reinterpret_cast<f4*>(A.rw[s] + base + k * 1024) = acc[k] * 0.5f;
+        }
+        if ((threadIdx.x & 7) == 0) {
+            const float t = acc[0].x + acc[1].y + acc[2].z + acc[3].w;
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                __builtin_nontemporal_store(__float_as_uint(t), A.small + ((size_t)s * gridDim.x * 4096 + base + k * 1024) / 32);
+        }
+    }
+    if (A.n_rw == 0) {      // read-only: keep the loads alive
+        const float t = acc[0].x + acc[1].y + acc[2].z + acc[3].w;
+        if (t == 1234.5678f) A.small[0] = 1u;
+    }
+}
+
+// write-heavy shapes of the utilities: a workgroup writes one tile of 4096 floats and reads READ_Q quarters
+// of a tile (0: pure fill; 1: the 1-byte-in / 4-bytes-out shape of a code-to-fp32 expansion)
+template <int READ_Q, bool NT = true>
+__global__ void __launch_bounds__(256) k_expand(const float* src, float* dst)
+{
+    const size_t base = (size_t)blockIdx.x * 4096 + threadIdx.x * 4;
+    f4 a = f4{1.f, 2.f, 3.f, 4.f};
+    if (READ_Q) a = __builtin_nontemporal_load(reinterpret_cast<const f4*>(src + (size_t)blockIdx.x * 1024 + threadIdx.x * 4));
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        if (NT) __builtin_nontemporal_store(a * (float)(k + 1), reinterpret_cast<f4*>(dst + base + k * 1024));
+        else *reinterpret_cast<f4*>(dst + base + k * 1024) = a * (float)(k + 1);
+    }
+}
+
 static void probe_streams()
 {
     const size_t n = (size_t)1 << 29;        // 2 GiB per stream
@@ -133,8 +188,29 @@ static void probe_streams()
         const float ms = best_ms([&] { hipLaunchKernelGGL(k_streams, dim3((unsigned)(n / 4096)), dim3(256), 0, 0, A); });
         const double bytes = (double)n * 4.0 * (c.ro + 2.0 * c.rw) + (double)c.rw * n / 8.0;
         std::printf("  %-84s %7.1f GB/s  (%.3f ms)\n", c.name, bytes / ms / 1e6, ms);
+        if (c.rw) {
+            const float ms2 = best_ms([&] { hipLaunchKernelGGL(k_streams_t<false>, dim3((unsigned)(n / 4096)), dim3(256), 0, 0, A); });
+            std::printf("  %-84s %7.1f GB/s  (%.3f ms)\n", "  the same with ordinary (cached) stores", bytes / ms2 / 1e6, ms2);
+        }
         std::fflush(stdout);
     }
+    {
+        const float ms = best_ms([&] { hipLaunchKernelGGL(k_expand<0>, dim3((unsigned)(n / 4096)), dim3(256), 0, 0, buf[0], buf[1]); });
+        std::printf("  %-84s %7.1f GB/s  (%.3f ms)\n", "1 write-only stream", (double)n * 4.0 / ms / 1e6, ms);
+    }
+    {
+        const float ms = best_ms([&] { hipLaunchKernelGGL((k_expand<0, false>), dim3((unsigned)(n / 4096)), dim3(256), 0, 0, buf[0], buf[1]); });
+        std::printf("  %-84s %7.1f GB/s  (%.3f ms)\n", "1 write-only stream, ordinary (cached) stores", (double)n * 4.0 / ms / 1e6, ms);
+    }
+    {
+        const float ms = best_ms([&] { hipLaunchKernelGGL(k_expand<1>, dim3((unsigned)(n / 4096)), dim3(256), 0, 0, buf[0], buf[1]); });
+        std::printf("  %-84s %7.1f GB/s  (%.3f ms)\n", "1 byte read per 4 bytes written (expansion of 8-bit codes to fp32)", (double)n * 5.0 / ms / 1e6, ms);
+    }
+    {
+        const float ms = best_ms([&] { hipLaunchKernelGGL((k_expand<1, false>), dim3((unsigned)(n / 4096)), dim3(256), 0, 0, buf[0], buf[1]); });
+        std::printf("  %-84s %7.1f GB/s  (%.3f ms)\n", "1 byte read per 4 bytes written, ordinary (cached) stores", (double)n * 5.0 / ms / 1e6, ms);
+    }
+    std::fflush(stdout);
     for (float* p : buf) CK(hipFree(p));
     CK(hipFree(small));
 }

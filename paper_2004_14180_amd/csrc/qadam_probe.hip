@@ -159,6 +159,40 @@ __global__ void __launch_bounds__(256) k_expand(const float* src, float* dst)
     }
 }
 
+// the main-pass shape once more with every lane's 128-bit access ld_off / st_off floats (0..3) off the 16-byte
+// grid (dword-aligned vector types): what a layer list whose offsets are not multiples of four costs
+typedef f4 f4_a4 __attribute__((aligned(4)));
+__global__ void __launch_bounds__(256) k_streams_off(StreamArgs A, int ld_off, int st_off)
+{
+    const size_t base = (size_t)blockIdx.x * 4096 + threadIdx.x * 4;
+    f4 acc[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) acc[k] = f4{0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < A.n_ro; ++s) {
+        f4 v[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v[k] = *reinterpret_cast<const f4_a4*>(A.ro[s] + base + k * 1024 + ld_off);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) acc[k] += v[k];
+    }
+    for (int s = 0; s < A.n_rw; ++s) {
+        f4 v[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v[k] = *reinterpret_cast<const f4_a4*>(A.rw[s] + base + k * 1024 + ld_off);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            acc[k] += v[k];
+            __builtin_nontemporal_store(acc[k] * 0.5f, reinterpret_cast<f4_a4*>(A.rw[s] + base + k * 1024 + st_off));
+        }
+        if ((threadIdx.x & 7) == 0) {
+            const float t = acc[0].x + acc[1].y + acc[2].z + acc[3].w;
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                __builtin_nontemporal_store(__float_as_uint(t), A.small + ((size_t)s * gridDim.x * 4096 + base + k * 1024) / 32);
+        }
+    }
+}
+
 static void probe_streams()
 {
     const size_t n = (size_t)1 << 29;        // 2 GiB per stream
@@ -191,6 +225,25 @@ static void probe_streams()
         if (c.rw) {
             const float ms2 = best_ms([&] { hipLaunchKernelGGL(k_streams_t<false>, dim3((unsigned)(n / 4096)), dim3(256), 0, 0, A); });
             std::printf("  %-84s %7.1f GB/s  (%.3f ms)\n", "  the same with ordinary (cached) stores", bytes / ms2 / 1e6, ms2);
+        }
+        std::fflush(stdout);
+    }
+    {
+        // grid one workgroup short, so that the shifted accesses of the last one stay inside the buffers
+        StreamArgs A;
+        std::memset(&A, 0, sizeof A);
+        A.n_ro = 8; A.n_rw = 12; A.small = small;
+        for (int i = 0; i < 8; ++i) A.ro[i] = buf[i];
+        for (int i = 0; i < 12; ++i) A.rw[i] = buf[8 + i];
+        const unsigned wgs = (unsigned)(n / 4096) - 1;
+        const double bytes = (double)wgs * 4096 * 4.0 * (8 + 24) + 12.0 * wgs * 4096 / 8.0;
+        const int offs[4][2] = {{0, 0}, {1, 1}, {1, 0}, {0, 1}};
+        const char* names[4] = {"main-pass shape through dword-aligned vector types, on the 16-byte grid (cached loads)",
+                                "  loads and stores 4 bytes off the grid", "  loads 4 bytes off the grid, stores on it",
+                                "  loads on the grid, stores 4 bytes off it"};
+        for (int c = 0; c < 4; ++c) {
+            const float ms = best_ms([&] { hipLaunchKernelGGL(k_streams_off, dim3(wgs), dim3(256), 0, 0, A, offs[c][0], offs[c][1]); });
+            std::printf("  %-84s %7.1f GB/s  (%.3f ms)\n", names[c], bytes / ms / 1e6, ms);
         }
         std::fflush(stdout);
     }

@@ -290,6 +290,42 @@ def test_layers_are_independent(oracle):
             assert part["scales"][i][0] == full["scales"][i][1]
 
 
+def test_zero_padding_of_layers_changes_nothing(oracle):
+    """A layer padded with zeros in every buffer gives the same results on its real elements, and the
+    padding stays zero: p = 0 quantizes to 0 for any scale and leaves no residual, a zero mean gradient
+    keeps m = v = 0 and moves x by alpha * 0 / sqrt(eps) = 0, and Q_x(0) = 0 (Sec. 5.1, Alg. 1).  This is
+    what lets a caller round layer lengths up to the access width of a device."""
+    sizes, N, steps = [1001, 7, 2500], 3, 4
+    pad = [(-n) % 4 for n in sizes]
+    segs = np.concatenate([[0], np.cumsum(sizes)])
+    psegs = np.concatenate([[0], np.cumsum([n + q for n, q in zip(sizes, pad)])])
+    P, PP = int(segs[-1]), int(psegs[-1])
+    real = np.concatenate([np.arange(psegs[l], psegs[l] + sizes[l]) for l in range(len(sizes))])
+    fill = np.setdiff1d(np.arange(PP), real)
+    rng = np.random.default_rng(77)
+    for flavor in (0, 1):
+        cfg = OracleConfig(k_g=2, k_x=6, weight_ef=1, adam_flavor=flavor)
+        x = (rng.standard_normal(P) * 0.02).astype(np.float32)
+        m, v, w = _zeros(P, 3); errs = _zeros(P, N)
+        xp = np.zeros(PP, np.float32); xp[real] = x
+        mp, vp, wp = _zeros(PP, 3); errp = _zeros(PP, N)
+        for t in range(1, steps + 1):
+            grads = [(rng.standard_normal(P) * 1e-2).astype(np.float32) for _ in range(N)]
+            gp = []
+            for g in grads:
+                z = np.zeros(PP, np.float32); z[real] = g; gp.append(z)
+            a = oracle.step_s(cfg, segs, t, 1e-3, 0.999, grads, errs, x, m, v, w)
+            b = oracle.step_s(cfg, psegs, t, 1e-3, 0.999, gp, errp, xp, mp, vp, wp)
+            for u, up in [(x, xp), (m, mp), (v, vp), (w, wp), (a["wcodes"], b["wcodes"])]:
+                assert np.array_equal(u, up[real]) and not up[fill].any()
+            for i in range(N):
+                assert np.array_equal(errs[i], errp[i][real]) and not errp[i][fill].any()
+                assert np.array_equal(a["scales"][i], b["scales"][i])
+                ca = oracle.unpack_all(cfg.k_g, segs, a["words"][i])
+                cb = oracle.unpack_all(cfg.k_g, psegs, b["words"][i])
+                assert np.array_equal(ca, cb[real]) and not cb[fill].any()
+
+
 def test_window_equals_layer(oracle):
     """Given the layer's scale, a window of the layer quantizes to the same codes."""
     n = 10000

@@ -240,10 +240,13 @@ def run_full_schedule(config, start_state, misalign=False, steps=None):
     wl = make_workload(config, misalign=misalign)
     if steps is not None:
         wl.steps = steps
+    return run_workload(wl, start_state, "config%d full%s" % (config, " misaligned" if misalign else ""))
+
+
+def run_workload(wl, start_state, tag):
     run = FullRun(wl, start_state=start_state)
     run.init_host_state()
     rep = Report()
-    tag = "config%d full%s" % (config, " misaligned" if misalign else "")
     for t in range(1, wl.steps + 1):
         wl.fill_gradients(t, run.grads)
         run.step(t)
@@ -281,3 +284,15 @@ def test_config5_gpt13b_full_size_off_alignment():
     a flat index = 1 mod 4 (the kernels then use their dword-aligned wide accesses everywhere): two steps,
     the second with the filtered scale pass, every layer and every element."""
     run_full_schedule(5, "synthetic", misalign=True, steps=2)
+
+
+def test_vector_beyond_2_to_31_elements():
+    """The largest shape the index arithmetic has to carry: a flat vector of more than 2^31 elements
+    (8.6 GB per buffer), with one layer that crosses element 2^31 and, behind it, an odd-sized layer and
+    layers that lie wholly beyond 2^31 off the 16-byte grid.  Two workers, gradients by config 2's
+    recipe, two steps (the second with the filtered scale pass), every element against the oracle."""
+    from paper_2004_14180_amd.workloads import Workload
+    sizes = [5000, (1 << 31) + 3 * 4096 + 77, 1001, 300000, 64, 2 * 4096]
+    wl = Workload(2, "beyond-2^31", sizes, 2, 2)
+    assert wl.seg_offsets[2] > (1 << 31) and wl.seg_offsets[3] % 4 != 0
+    run_workload(wl, "synthetic", "2^31+ elements")

@@ -557,8 +557,8 @@ def main():
                          "allocation per buffer")
     ap.add_argument("--misalign", action="store_true",
                     help="put one 1001-element layer in front of the workload's layer list, so that every other "
-                         "layer starts off a 16-byte boundary (the kernels then shift data between lanes to keep "
-                         "their memory accesses aligned)")
+                         "layer starts off a 16-byte boundary (the kernels then move their data with 4-byte-aligned "
+                         "128-bit accesses)")
     ap.add_argument("--graph", action="store_true",
                     help="capture the step in a HIP graph after the warm-up and time replays of it (pays on "
                          "launch-bound workloads such as config 1; kernels are then not timed one by one)")

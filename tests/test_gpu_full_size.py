@@ -46,6 +46,17 @@ def _host(t):
     return h
 
 
+def _pull(t):
+    """A whole device tensor as a numpy array, copied piece by piece through pinned staging."""
+    out = np.empty(t.numel(), np.float32)
+    for c in range(0, t.numel(), 1 << 26):
+        d = min(t.numel(), c + (1 << 26))
+        h = _host(t[c:d])
+        torch.cuda.current_stream().synchronize()
+        out[c:d] = h.numpy()
+    return out
+
+
 class FullRun:
     """Device buffers of a workload, the oracle's complete state on the host, and the streaming
     comparison of a step."""
@@ -78,16 +89,8 @@ class FullRun:
 
     def init_host_state(self):
         """The oracle's state: host copies of the seeded start state (taken before the first step)."""
-        def pull(t):
-            out = np.empty(t.numel(), np.float32)
-            for c in range(0, t.numel(), 1 << 26):
-                d = min(t.numel(), c + (1 << 26))
-                h = _host(t[c:d])
-                torch.cuda.current_stream().synchronize()
-                out[c:d] = h.numpy()
-            return out
-        self.host = dict(errs=[pull(e) for e in self.errs], x=pull(self.x), m=pull(self.m), v=pull(self.v),
-                         werr=pull(self.werr))
+        self.host = dict(errs=[_pull(e) for e in self.errs], x=_pull(self.x), m=_pull(self.m), v=_pull(self.v),
+                         werr=_pull(self.werr))
 
     def step(self, t):
         wl = self.wl
@@ -296,3 +299,121 @@ def test_vector_beyond_2_to_31_elements():
     wl = Workload(2, "beyond-2^31", sizes, 2, 2)
     assert wl.seg_offsets[2] > (1 << 31) and wl.seg_offsets[3] % 4 != 0
     run_workload(wl, "synthetic", "2^31+ elements")
+
+
+# ------------------------------------------------------------------------------------------------
+class FullRunW(FullRun):
+    """Variant W (Algorithms 2-3: the workers own the moments and quantize the update) at full size.
+    The server has no m, v here; every worker has its own, on the device and in the oracle's host state.
+    The scale of a layer is the maximum of a quantity the oracle itself computes (alpha m' / sqrt(v' +
+    eps) + e), so every layer goes through the oracle whole, largest first, one layer per thread."""
+
+    def __init__(self, wl):
+        super().__init__(wl, start_state="synthetic")
+        self.q.trust_error_buffers(False)       # the scale pass of variant W has no filtered form
+        # per-worker moments: the synthetic server moments, scaled differently per worker
+        self.mw = [self.m * (1.0 + 0.125 * i) for i in range(wl.num_workers)]
+        self.vw = [self.v * (1.0 + 0.25 * i) for i in range(wl.num_workers)]
+        del self.m, self.v
+
+    def init_host_state(self):
+        self.host = dict(errs=[_pull(e) for e in self.errs], mw=[_pull(u) for u in self.mw],
+                         vw=[_pull(u) for u in self.vw], x=_pull(self.x), werr=_pull(self.werr))
+
+    def step(self, t):
+        wl = self.wl
+        self.q.step_fused_w(t, wl.lr, wl.beta2, self.grads, self.mw, self.vw, self.errs, self.codes, self.scales,
+                            self.x, self.werr, self.wcodes)
+        torch.cuda.synchronize()
+        assert self.q.get_status() == 0
+
+    def check_step(self, rep, t, progress=""):
+        wl = self.wl
+        N = wl.num_workers
+        lock = threading.Lock()
+        dscales = [s.cpu().numpy() for s in self.scales]
+        inflight = threading.Semaphore(THREADS)
+        h = self.host
+
+        def layer(l, a, b, grads, got):
+            try:
+                n = b - a
+                he, hm, hv = ([u[a:b] for u in h[k]] for k in ("errs", "mw", "vw"))
+                hx, hw = h["x"][a:b], h["werr"][a:b]
+                out = oracle.step_w(self.ocfg, [0, n], t, wl.lr, wl.beta2, [g.numpy() for g in grads],
+                                    he, hm, hv, hx, hw, index_base=a)
+                assert out["status"] == 0
+                local = Report()
+                skip = np.zeros(n, bool)
+                for i in range(N):
+                    assert dscales[i][l].view(np.uint32) == out["scales"][i][0].view(np.uint32), \
+                        "step %d: scale of worker %d, layer %d" % (t, i, l)
+                    gc = oracle.unpack_codes(self.bits, got["words"][i].numpy().view(np.uint32), n)
+                    diff = gc != oracle.unpack_codes(self.bits, out["words"][i], n)
+                    if diff.any():
+                        local.code_mismatch += int(diff.sum())
+                        assert not (diff & (out["tie_g"][i] == 0)).any(), \
+                            "step %d layer %d: worker %d code mismatch on unflagged elements" % (t, l, i)
+                        skip |= diff
+                    local.ties_g += int(np.count_nonzero(out["tie_g"][i]))
+                    close(local, "err", got["errs"][i].numpy(), he[i], diff if diff.any() else None)
+                    close(local, "mw", got["mw"][i].numpy(), hm[i])
+                    close(local, "vw", got["vw"][i].numpy(), hv[i])
+                assert not skip.any(), "a flagged code difference would need the excused-element bookkeeping"
+                close(local, "x", got["x"].numpy(), hx)
+                wdiff = got["wcodes"].numpy() != out["wcodes"]
+                local.wcode_mismatch += int(wdiff.sum())
+                local.ties_x += int(np.count_nonzero(out["tie_x"]))
+                assert not wdiff.any(), "step %d layer %d: weight codes" % (t, l)
+                close(local, "werr", got["werr"].numpy(), hw)
+                with lock:
+                    for f in ("code_mismatch", "wcode_mismatch", "ties_g", "ties_x", "float_not_bit_exact"):
+                        setattr(rep, f, getattr(rep, f) + getattr(local, f))
+                    rep.checked += n * (N + 1)
+                    rep.max_rel = max(rep.max_rel, local.max_rel)
+                    if progress and n >= (1 << 22):
+                        _say("%s: layer %d (%d elements) done" % (progress, l, n))
+            finally:
+                inflight.release()
+
+        futures = []
+        with ThreadPoolExecutor(THREADS) as ex:
+            for l in sorted(range(len(wl.sizes)), key=lambda l: -wl.sizes[l]):
+                a, b = self.seg[l], self.seg[l + 1]
+                if b == a:
+                    continue
+                inflight.acquire()
+                w0 = self.woffs[l]
+                nw = (b - a + 31) // 32 * self.bits
+                grads = [_host(g[a:b]) for g in self.grads]
+                got = dict(errs=[_host(e[a:b]) for e in self.errs], mw=[_host(u[a:b]) for u in self.mw],
+                           vw=[_host(u[a:b]) for u in self.vw], x=_host(self.x[a:b]), werr=_host(self.werr[a:b]),
+                           wcodes=_host(self.wcodes[a:b]), words=[_host(c[w0:w0 + nw]) for c in self.codes])
+                torch.cuda.current_stream().synchronize()
+                futures.append(ex.submit(layer, l, a, b, grads, got))
+                for f in [f for f in futures if f.done()]:
+                    f.result()
+                    futures.remove(f)
+            for f in futures:
+                f.result()
+
+
+def test_config5_gpt13b_full_size_variant_w():
+    """Config 5 at full size through qadam_step_fused_w (Algorithms 2-3 as printed: 16 more P-sized
+    buffers for the workers' moments, 190 GB on the device), as `bench.py --variant w` launches it:
+    two steps from a synthetic mid-training state, every layer and every element against the oracle
+    (the second step starts from the residuals the first one left in the error buffers, which this
+    variant also uses to park the update between its two passes)."""
+    wl = make_workload(5)
+    wl.steps = 2
+    run = FullRunW(wl)
+    run.init_host_state()
+    rep = Report()
+    for t in range(1, wl.steps + 1):
+        wl.fill_gradients(t, run.grads)
+        run.step(t)
+        run.check_step(rep, t, progress="config5 variant W step %d" % t)
+        _say("config5 variant W step %d/%d (every layer, every element): %s" % (t, wl.steps, rep.line()))
+        assert rep.ok()
+    assert rep.checked == wl.steps * wl.num_params * (wl.num_workers + 1)
+    run.q.close()

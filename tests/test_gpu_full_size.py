@@ -35,6 +35,25 @@ WHOLE_LAYER_MAX = 1 << 22     # layers up to this many elements go through the o
 CHUNK = 1 << 21               # larger layers: chunks of this many elements (a multiple of 32)
 
 
+@pytest.fixture(autouse=True)
+def _release_cached_memory():
+    """Each test here stages tens of GB through pinned host memory in pieces of its own sizes and fills most
+    of the device: hand what the previous test's allocators still cache (pinned host blocks, device blocks)
+    back before and after, so that no test depends on what ran before it."""
+    import gc
+
+    def release():
+        gc.collect()
+        torch.cuda.synchronize()
+        torch.cuda.empty_cache()
+        empty_host = getattr(torch._C, "_host_emptyCache", None)
+        if empty_host is not None:
+            empty_host()
+    release()
+    yield
+    release()
+
+
 def _say(msg):
     print(msg, flush=True)
 
@@ -61,11 +80,13 @@ class FullRun:
     """Device buffers of a workload, the oracle's complete state on the host, and the streaming
     comparison of a step."""
 
-    def __init__(self, wl, start_state="synthetic"):
+    def __init__(self, wl, start_state="synthetic", rounding=0, path="fused"):
         self.wl = wl
         dev = torch.device("cuda:0")
         self.dev = dev
-        self.gcfg, self.ocfg = configs(k_g=wl.k_g, k_x=wl.k_x, weight_ef=1, beta1=wl.beta1, eps=wl.eps)
+        self.path = path
+        self.gcfg, self.ocfg = configs(k_g=wl.k_g, k_x=wl.k_x, weight_ef=1, beta1=wl.beta1, eps=wl.eps,
+                                       rounding=rounding, seed=wl.seed + 17)
         self.seg = wl.seg_offsets
         self.q = QAdam(self.gcfg, self.seg, wl.num_workers)
         # as the benchmark runs it: from the second step of a handle on, the scale pass is the filtered one
@@ -94,8 +115,14 @@ class FullRun:
 
     def step(self, t):
         wl = self.wl
-        self.q.step_fused(t, wl.lr, wl.beta2, self.grads, self.errs, self.codes, self.scales,
-                          self.x, self.m, self.v, self.werr, self.wcodes)
+        if self.path == "fused":
+            self.q.step_fused(t, wl.lr, wl.beta2, self.grads, self.errs, self.codes, self.scales,
+                              self.x, self.m, self.v, self.werr, self.wcodes)
+        else:       # the same step as the separate calls of the boundary
+            for i in range(wl.num_workers):
+                self.q.worker_quantize(i, t, self.grads[i], self.errs[i], self.codes[i], self.scales[i])
+            self.q.server_step(t, wl.lr, wl.beta2, self.codes, self.scales, self.x, self.m, self.v)
+            self.q.weight_quantize(t, self.x, self.werr, self.wcodes)
         torch.cuda.synchronize()
         assert self.q.get_status() == 0
 
@@ -246,8 +273,8 @@ def run_full_schedule(config, start_state, misalign=False, steps=None):
     return run_workload(wl, start_state, "config%d full%s" % (config, " misaligned" if misalign else ""))
 
 
-def run_workload(wl, start_state, tag):
-    run = FullRun(wl, start_state=start_state)
+def run_workload(wl, start_state, tag, **kw):
+    run = FullRun(wl, start_state=start_state, **kw)
     run.init_host_state()
     rep = Report()
     for t in range(1, wl.steps + 1):
@@ -289,16 +316,29 @@ def test_config5_gpt13b_full_size_off_alignment():
     run_full_schedule(5, "synthetic", misalign=True, steps=2)
 
 
-def test_vector_beyond_2_to_31_elements():
+@pytest.mark.parametrize("rounding", [0, 1])
+def test_vector_beyond_2_to_31_elements(rounding):
     """The largest shape the index arithmetic has to carry: a flat vector of more than 2^31 elements
     (8.6 GB per buffer), with one layer that crosses element 2^31 and, behind it, an odd-sized layer and
     layers that lie wholly beyond 2^31 off the 16-byte grid.  Two workers, gradients by config 2's
-    recipe, two steps (the second with the filtered scale pass), every element against the oracle."""
+    recipe, two steps (the second with the filtered scale pass), every element against the oracle;
+    with stochastic rounding as well, whose random stream is indexed by the flat element number."""
     from paper_2004_14180_amd.workloads import Workload
     sizes = [5000, (1 << 31) + 3 * 4096 + 77, 1001, 300000, 64, 2 * 4096]
     wl = Workload(2, "beyond-2^31", sizes, 2, 2)
     assert wl.seg_offsets[2] > (1 << 31) and wl.seg_offsets[3] % 4 != 0
-    run_workload(wl, "synthetic", "2^31+ elements")
+    run_workload(wl, "synthetic", "2^31+ elements, rounding %d" % rounding, rounding=rounding)
+
+
+def test_config5_gpt13b_full_size_separate_calls():
+    """Config 5 at full size through the separate calls of the boundary (8 x qadam_worker_quantize,
+    qadam_server_step, qadam_weight_quantize: the codes go through memory and are decoded again), as
+    `bench.py --path calls` launches it: one step from a synthetic mid-training state, every layer and
+    every element against the oracle (the filtered scale pass of the worker call, which a second step
+    would use, is covered at smaller sizes)."""
+    wl = make_workload(5)
+    wl.steps = 1
+    run_workload(wl, "synthetic", "config5 separate calls", path="calls")
 
 
 # ------------------------------------------------------------------------------------------------

@@ -531,6 +531,7 @@ def test_variant_w_fused_step(N, rounding):
     q.close()
 
 
+@pytest.mark.filterwarnings("ignore:The CUDA Graph is empty")     # the two refused captures record nothing
 def test_step_is_capturable_in_a_hip_graph():
     """The compute calls only enqueue kernels (no allocation, no memset, no synchronisation), so a
     step can be captured once and replayed; every replay must equal the eager call on a twin state."""

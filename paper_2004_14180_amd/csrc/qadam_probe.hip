@@ -64,7 +64,8 @@ static float best_ms(F launch, int reps = 5)
 constexpr int kMaxStreams = 24;
 struct StreamArgs {
     const float* ro[kMaxStreams];   // read-only streams
-    float* rw[kMaxStreams];         // updated in place
+    float* rw[kMaxStreams];         // updated in place ...
+    float* wo[kMaxStreams];         // ... or, where non-null, read from rw[s] and written here (out of place)
     unsigned* small;                // one word per 32 elements and updated stream (stands in for the packed codes)
     int n_ro, n_rw;
 };
@@ -75,6 +76,7 @@ __global__ void __launch_bounds__(256) k_streams_t(StreamArgs A);
 __global__ void __launch_bounds__(256) k_streams(StreamArgs A)
 {
     const size_t base = (size_t)blockIdx.x * 4096 + threadIdx.x * 4;
+    const bool out_of_place = A.wo[0] != nullptr;
     f4 acc[4];
 #pragma unroll
     for (int k = 0; k < 4; ++k) acc[k] = f4{0.f, 0.f, 0.f, 0.f};
@@ -89,10 +91,11 @@ __global__ void __launch_bounds__(256) k_streams(StreamArgs A)
         f4 v[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) v[k] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(A.rw[s] + base + k * 1024));
+        float* dst = out_of_place ? A.wo[s] : A.rw[s];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             acc[k] += v[k];
-            __builtin_nontemporal_store(acc[k] * 0.5f, reinterpret_cast<f4*>(A.rw[s] + base + k * 1024));
+            __builtin_nontemporal_store(acc[k] * 0.5f, reinterpret_cast<f4*>(dst + base + k * 1024));
         }
         if ((threadIdx.x & 7) == 0) {
             const float t = acc[0].x + acc[1].y + acc[2].z + acc[3].w;
@@ -318,6 +321,35 @@ static void probe_placement()
         }
         std::snprintf(name, sizeof name, "dealt alternately to %d equal parts of the block", groups);
         run(name, offs);
+    }
+    // the same 20 reads and 13 writes with every updated stream written to a second buffer instead of in place
+    // (32 buffers): does it pay to keep what is read and what is written in different parts of the memory?
+    auto run_oop = [&](const char* name, const std::vector<size_t>& rd, const std::vector<size_t>& wr) {
+        StreamArgs A;
+        std::memset(&A, 0, sizeof A);
+        A.n_ro = 8; A.n_rw = 12; A.small = small;
+        for (size_t o : rd) if (o + buf > arena_bytes) { std::printf("  %-58s does not fit\n", name); return; }
+        for (size_t o : wr) if (o + buf > arena_bytes) { std::printf("  %-58s does not fit\n", name); return; }
+        for (int i = 0; i < 12; ++i) A.rw[i] = reinterpret_cast<float*>(arena + rd[i]);
+        for (int i = 0; i < 8; ++i) A.ro[i] = reinterpret_cast<const float*>(arena + rd[12 + i]);
+        for (int i = 0; i < 12; ++i) A.wo[i] = reinterpret_cast<float*>(arena + wr[i]);
+        const float ms = best_ms([&] { hipLaunchKernelGGL(k_streams, dim3((unsigned)(n / 4096)), dim3(256), 0, 0, A); }, 3);
+        const double bytes = (double)n * 4.0 * (8 + 2.0 * 12) + 12.0 * n / 8.0;
+        std::printf("  %-58s %7.1f GB/s  (%.3f ms)\n", name, bytes / ms / 1e6, ms);
+        std::fflush(stdout);
+    };
+    if (arena_bytes >= 136 * GiB) {
+        const size_t half = arena_bytes / 2 / GiB * GiB;
+        std::vector<size_t> rd(20), wr(12);
+        for (int i = 0; i < 20; ++i) rd[i] = (size_t)i * buf;
+        for (int i = 0; i < 12; ++i) wr[i] = half + (size_t)i * buf;
+        run_oop("out of place: 20 read from the lower half, 12 written to the upper", rd, wr);
+        for (int i = 0; i < 20; ++i) rd[i] = (size_t)(i & 1) * half + (size_t)(i / 2) * buf;
+        for (int i = 0; i < 12; ++i) wr[i] = (size_t)((i + 1) & 1) * half + (size_t)(10 + i / 2) * buf;
+        run_oop("out of place: reads and writes dealt to both halves", rd, wr);
+        for (int i = 0; i < 20; ++i) rd[i] = (size_t)i * buf;
+        for (int i = 0; i < 12; ++i) wr[i] = (size_t)(20 + i) * buf;
+        run_oop("out of place: all 32 buffers packed back to back from 0", rd, wr);
     }
     CK(hipFree(small));
     CK(hipFree(arena));

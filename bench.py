@@ -165,13 +165,14 @@ def measure_ceilings(dev):
 
 # ---------------------------------------------------------------------------------------- utilities
 def bench_utilities(wl, dev, reps=5):
-    """The kernels around the step (what a worker does with the broadcast weight codes; the norm diagnostic;
-    the check of the filtered pass's contract), each timed alone with HIP events on the stream the library
-    launches on, against its algorithmic bytes."""
+    """The kernels around the step (what a worker does with the broadcast weight codes; the norm diagnostic),
+    each timed alone with HIP events on the stream the library launches on, against its algorithmic bytes.
+    Twice: with one allocation per buffer, and with the buffers spread over one block that spans the device
+    (input at 1/4, codes at 1/2, output at 3/4 of it) -- where the buffers lie matters for these kernels as it
+    does for the step."""
     import torch
     from paper_2004_14180_amd import QAdam, QAdamConfig
     P, N = wl.num_params, 1
-    out = {}
 
     def timed(fn):
         ms = []
@@ -183,34 +184,58 @@ def bench_utilities(wl, dev, reps=5):
         ms = ms[1:]
         return sum(ms) / len(ms)
 
-    def entry(name, bytes_per_param, ms):
-        gbs = bytes_per_param * P / (ms * 1e-3) / 1e9
-        out[name] = {"avg_launch_ms": round(ms, 4), "algorithmic_bytes_per_param": bytes_per_param,
-                     "achieved_GBs": round(gbs, 1), "frac": round(gbs / HBM_PEAK_GBS, 4)}
+    def measure(alloc):
+        """alloc(which, dtype) -> a P-element tensor; which in 'in', 'codes', 'out'."""
+        out = {}
 
-    x = wl.init_weights(dev)
-    for k_x, dt in ((6, torch.int8), (14, torch.int16)):
-        q = QAdam(QAdamConfig(k_g=wl.k_g, k_x=k_x, weight_ef=0, beta1=wl.beta1, eps=wl.eps), wl.seg_offsets, N)
-        wcodes = torch.empty(P, dtype=dt, device=dev)
-        werr = torch.empty(P, dtype=torch.float32, device=dev)
-        nb = wcodes.element_size()
-        entry("qadam_weight_quantize, int%d codes, weight_ef=0 (k_weight_quantize)" % (8 * nb), 8.0 + nb,
-              timed(lambda: q.weight_quantize(1, x, werr, wcodes)))
-        xhat = werr                                     # reuse the buffer
-        entry("qadam_weight_dequantize, int%d -> fp32 (k_weight_dequantize)" % (8 * nb), 4.0 + nb,
-              timed(lambda: q.weight_dequantize(wcodes, xhat)))
-        xh16 = torch.empty(P, dtype=torch.float16, device=dev)
-        entry("qadam_weight_dequantize_f16, int%d -> binary16 (k_weight_dequantize)" % (8 * nb), 2.0 + nb,
-              timed(lambda: q.weight_dequantize_f16(wcodes, xh16)))
-        if k_x == 6:
-            sums = torch.empty(q.num_segments, dtype=torch.float64, device=dev)
-            entry("qadam_layer_sumsq(a, b) (k_sumsq_tiles + k_sumsq_layers)", 8.0, timed(lambda: q.layer_sumsq(x, werr, sums)))
-            entry("qadam_layer_sumsq(a) (k_sumsq_tiles + k_sumsq_layers)", 4.0, timed(lambda: q.layer_sumsq(x, None, sums)))
-            del sums
-        del wcodes, werr, xh16, xhat
-        q.close()
+        def entry(name, bytes_per_param, ms):
+            gbs = bytes_per_param * P / (ms * 1e-3) / 1e9
+            out[name] = {"avg_launch_ms": round(ms, 4), "algorithmic_bytes_per_param": bytes_per_param,
+                         "achieved_GBs": round(gbs, 1), "frac": round(gbs / HBM_PEAK_GBS, 4)}
+
+        x = alloc("in", torch.float32)
+        x.copy_(wl.init_weights(dev))
+        for k_x, dt in ((6, torch.int8), (14, torch.int16)):
+            q = QAdam(QAdamConfig(k_g=wl.k_g, k_x=k_x, weight_ef=0, beta1=wl.beta1, eps=wl.eps), wl.seg_offsets, N)
+            wcodes = alloc("codes", dt)
+            werr = alloc("out", torch.float32)
+            nb = wcodes.element_size()
+            entry("qadam_weight_quantize, int%d codes, weight_ef=0 (k_weight_quantize)" % (8 * nb), 8.0 + nb,
+                  timed(lambda: q.weight_quantize(1, x, werr, wcodes)))
+            xhat = werr                                     # reuse the buffer
+            entry("qadam_weight_dequantize, int%d -> fp32 (k_weight_dequantize)" % (8 * nb), 4.0 + nb,
+                  timed(lambda: q.weight_dequantize(wcodes, xhat)))
+            xh16 = alloc("out", torch.float16)
+            entry("qadam_weight_dequantize_f16, int%d -> binary16 (k_weight_dequantize)" % (8 * nb), 2.0 + nb,
+                  timed(lambda: q.weight_dequantize_f16(wcodes, xh16)))
+            if k_x == 6:
+                sums = torch.empty(q.num_segments, dtype=torch.float64, device=dev)
+                werr.normal_(0.0, 1e-3)
+                entry("qadam_layer_sumsq(a, b) (k_sumsq_tiles + k_sumsq_layers)", 8.0, timed(lambda: q.layer_sumsq(x, werr, sums)))
+                entry("qadam_layer_sumsq(a) (k_sumsq_tiles + k_sumsq_layers)", 4.0, timed(lambda: q.layer_sumsq(x, None, sums)))
+                del sums
+            del wcodes, werr, xh16, xhat
+            q.close()
+        return out
+
+    result = {"one allocation per buffer": measure(lambda which, dt: torch.empty(P, dtype=dt, device=dev))}
     torch.cuda.empty_cache()
-    return out
+    free_b, _ = torch.cuda.mem_get_info()
+    block_bytes = (free_b - (8 << 30)) >> 30 << 30
+    try:
+        block = torch.empty(block_bytes, dtype=torch.uint8, device=dev)
+    except RuntimeError:
+        block = None
+    if block is not None and block_bytes >= 16 * P:
+        where = {"in": block_bytes // 4, "codes": block_bytes // 2, "out": block_bytes // 4 * 3}
+
+        def carve(which, dt):
+            nbytes = P * torch.empty(0, dtype=dt).element_size()
+            return block[where[which]:where[which] + nbytes].view(dt)
+        result["one block of %d bytes: input at 1/4, codes at 1/2, output at 3/4" % block_bytes] = measure(carve)
+    del block
+    torch.cuda.empty_cache()
+    return result
 
 
 # ------------------------------------------------------------------------------------- CPU baseline

@@ -21,6 +21,12 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-ffp-contract=off", "-fno-fast-math",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # The kernels take their arguments as one struct with per-worker pointer arrays that are indexed at run
+    # time.  The compiler reads such a struct straight from the kernel-argument segment only if a use scan of
+    # bounded length succeeds (default 300 uses); the fused kernel, with its tile loop instantiated for each
+    # layer kind, has more, and past the bound the whole 1.2 KB struct is copied to per-lane scratch memory
+    # at kernel entry.  tests/test_library_boundary.py checks that no kernel has a scratch segment.
+    "-mllvm", "-instcombine-max-copied-from-constant-users=4000",
     "-Wall", "-Wno-unused-function",
 ]
 
@@ -56,6 +62,29 @@ def device_assembly(source: str = "qadam_kernels.hip", packed_fp32_off: bool = T
     cmd = [hipcc(), *flags, "--cuda-device-only", "-S", "-I", os.path.join(HERE, "..", "include"), "-o", "-",
            os.path.join(CSRC, source)]
     return subprocess.run(cmd, check=True, capture_output=True, text=True).stdout
+
+
+def device_resource_usage(source: str = "qadam_kernels.hip") -> dict:
+    """Registers, scratch and LDS of every kernel of one of this package's sources, as the compiler reports
+    them for the library's flags: {demangled-ish kernel name: {"vgprs", "sgprs", "scratch_bytes", "lds_bytes",
+    "waves_per_simd"}}."""
+    import re
+    flags = [f for f in HIPCC_FLAGS if f not in ("-fPIC", "-shared")]
+    cmd = [hipcc(), *flags, "--cuda-device-only", "-c", "-Rpass-analysis=kernel-resource-usage",
+           "-I", os.path.join(HERE, "..", "include"), "-o", os.devnull, os.path.join(CSRC, source)]
+    text = subprocess.run(cmd, check=True, capture_output=True, text=True).stderr
+    out, cur = {}, None
+    keys = {"VGPRs": "vgprs", "TotalSGPRs": "sgprs", "ScratchSize [bytes/lane]": "scratch_bytes",
+            "LDS Size [bytes/block]": "lds_bytes", "Occupancy [waves/SIMD]": "waves_per_simd"}
+    for line in text.splitlines():
+        m = re.search(r"remark:\s+Function Name: (\S+)", line)
+        if m:
+            cur = out.setdefault(m.group(1), {})
+            continue
+        m = re.search(r"remark:\s+([A-Za-z \[\]/]+): (\d+)", line)
+        if m and cur is not None and m.group(1).strip() in keys:
+            cur[keys[m.group(1).strip()]] = int(m.group(2))
+    return out
 
 
 def build_library(verbose: bool = True) -> str:

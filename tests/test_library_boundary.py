@@ -78,3 +78,20 @@ def test_device_code_holds_no_packed_fp32_instructions():
     assert "k_fused" in asm and "gfx950" in asm
     packed = re.findall(r"\bv_pk_(?:add|mul|fma)_f32\b", asm)
     assert not packed, "%d packed fp32 instructions in the device code" % len(packed)
+
+
+def test_kernels_keep_their_arguments_out_of_scratch_and_the_main_pass_its_occupancy():
+    """What the compiler reports for the library's kernels under the library's flags.  No kernel may have a
+    per-lane scratch segment to speak of: the kernels take one argument struct with pointer arrays indexed
+    at run time, and when the compiler cannot prove it can read that struct in place it copies all of it
+    (1.2 KB for the fused kernel) to scratch at kernel entry and reads every pointer back from there, silently.
+    The fused main pass in the benchmark's configuration (nearest rounding, four workers' loads in flight,
+    variant S) must also stay within 96 vector registers, i.e. five wavefronts per SIMD."""
+    from paper_2004_14180_amd.build import device_resource_usage
+    usage = device_resource_usage("qadam_kernels.hip")
+    assert len(usage) >= 30, "kernel list not parsed"
+    for name, u in usage.items():
+        assert u["scratch_bytes"] <= 64, "%s: %d bytes of scratch per lane" % (name, u["scratch_bytes"])
+    main = [u for name, u in usage.items() if "k_fusedILi0ELi4ELb0" in name]
+    assert len(main) == 1
+    assert main[0]["scratch_bytes"] == 0 and main[0]["vgprs"] <= 96 and main[0]["waves_per_simd"] >= 5, main[0]
